@@ -1,0 +1,179 @@
+"""FastKV selection-path oracle (TEST INFRASTRUCTURE ONLY).
+
+numpy front end of ``fastkv_oracle.c``: plain CPU loops for the window-attention
+saliency score (Sec. 4.2, Eq. 1), per-head pooling, group / all-head means (Eq. 2,
+App. B.1), top-k with the window merged in (Sec. 4.2) and the row gathers of
+HiddenCompress / KVCompress (App. B.1, Algorithm 1).  Only tests, the smoke check and
+the benchmark's CPU-baseline leg may import this package; it shares nothing with the
+GPU library.
+
+bf16 tensors are carried as ``uint16`` bit patterns.  ``precision`` picks the fp32
+build (``"f32"``, accumulates like the GPU path's arithmetic type) or the fp64 build
+(``"f64"``, used to bound rounding).
+"""
+import ctypes
+import math
+
+import numpy as np
+
+from . import build as _build
+
+POOL_AVG = 0
+POOL_MAX = 1
+_POOL = {"avg": POOL_AVG, "max": POOL_MAX, POOL_AVG: POOL_AVG, POOL_MAX: POOL_MAX}
+
+_libs = {}
+
+
+def _lib(precision: str):
+    if precision not in ("f32", "f64"):
+        raise ValueError("precision must be 'f32' or 'f64'")
+    if precision not in _libs:
+        paths = _build.build()
+        lib = ctypes.CDLL(paths[precision])
+        assert lib.orc_real_bytes() == (4 if precision == "f32" else 8)
+        _libs[precision] = lib
+    return _libs[precision]
+
+
+def max_threads():
+    """Threads the head loop of window_attention will use (OpenMP over heads only)."""
+    return int(_lib("f32").orc_max_threads())
+
+
+def _real(precision):
+    return np.float32 if precision == "f32" else np.float64
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u16(a, shape_len):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint16 or a.ndim != shape_len:
+        raise ValueError("bf16 tensors are passed as uint16 bit patterns with %d dims" % shape_len)
+    return a
+
+
+def window_attention(q_win, k, scale=None, causal=True, precision="f32", threads=None):
+    """s[h, j] = sum over the W window queries of the softmax attention row at key j (Eq. 1
+    before pooling), j in the prefix [0, L-W).  q_win [W,Hq,d], k [L,Hkv,d] (uint16 bf16)."""
+    q_win, k = _u16(q_win, 3), _u16(k, 3)
+    W, Hq, d = q_win.shape
+    L, Hkv, d2 = k.shape
+    if d2 != d:
+        raise ValueError("head_dim mismatch")
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    P = L - W
+    out = np.empty((Hq, P), dtype=_real(precision))
+    lib = _lib(precision)
+    if threads is not None:
+        lib.orc_set_threads(int(threads))
+    rc = lib.orc_window_attention(_ptr(q_win), _ptr(k), L, Hq, Hkv, d, W, ctypes.c_double(scale),
+                                  int(bool(causal)), _ptr(out))
+    if rc != 0:
+        raise ValueError("orc_window_attention failed: %d" % rc)
+    return out
+
+
+def pool_rows(s, kernel=7, mode="max", precision="f32"):
+    """Same-length 1-D pooling along the last axis of s [rows, P] (Eq. 1 'Pooling')."""
+    s = np.ascontiguousarray(s, dtype=_real(precision))
+    rows, P = s.shape
+    out = np.empty_like(s)
+    lib = _lib(precision)
+    for r in range(rows):
+        rc = lib.orc_pool_row(_ptr(s[r]), P, int(kernel), _POOL[mode], _ptr(out[r]))
+        if rc != 0:
+            raise ValueError("orc_pool_row failed: %d" % rc)
+    return out
+
+
+def head_means(p_head, n_kv_heads, precision="f32"):
+    """(S_group [Hkv,P], S_tsp [P]) from pooled per-head scores [Hq,P] (App. B.1, Eq. 2)."""
+    p_head = np.ascontiguousarray(p_head, dtype=_real(precision))
+    Hq, P = p_head.shape
+    sg = np.empty((n_kv_heads, P), dtype=p_head.dtype)
+    st = np.empty((P,), dtype=p_head.dtype)
+    rc = _lib(precision).orc_head_means(_ptr(p_head), Hq, int(n_kv_heads), P, _ptr(sg), _ptr(st))
+    if rc != 0:
+        raise ValueError("orc_head_means failed: %d" % rc)
+    return sg, st
+
+
+def score_window(q_win, k, pool_kernel=7, pool_mode="max", scale=None, causal=True,
+                 precision="f32", threads=None):
+    """Full scoring of one sequence.  Returns dict with s_head, p_head [Hq,P],
+    scores_group [Hkv,P], scores_tsp [P] in the chosen precision."""
+    s_head = window_attention(q_win, k, scale, causal, precision, threads)
+    p_head = pool_rows(s_head, pool_kernel, pool_mode, precision)
+    sg, st = head_means(p_head, k.shape[1], precision)
+    return {"s_head": s_head, "p_head": p_head, "scores_group": sg, "scores_tsp": st}
+
+
+def select_topk(scores, window, k):
+    """Ascending kept indices of one row: the k-W best prefix tokens (ties to the lower
+    index) plus the W window tokens P..P+W-1 (Sec. 4.2).  scores are ranked as fp32."""
+    scores = np.ascontiguousarray(scores, dtype=np.float32)
+    if scores.ndim != 1:
+        raise ValueError("one row at a time")
+    P = scores.shape[0]
+    out = np.empty((int(k),), dtype=np.int32)
+    rc = _lib("f32").orc_select_topk(_ptr(scores), P, int(window), int(k), _ptr(out))
+    if rc != 0:
+        raise ValueError("orc_select_topk failed: %d (need W <= k <= P+W)" % rc)
+    return out
+
+
+def gather_rows(x, idx):
+    """out[t] = x[idx[t]] copied bit for bit; x is any C-contiguous array, rows on axis 0."""
+    x = np.ascontiguousarray(x)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    if idx.size and (idx.min() < 0 or idx.max() >= x.shape[0]):
+        raise IndexError("gather index out of range")
+    row_bytes = x.strides[0] if x.ndim > 1 else x.itemsize
+    out = np.empty((idx.shape[0],) + x.shape[1:], dtype=x.dtype)
+    _lib("f32").orc_gather_rows(_ptr(x), ctypes.c_size_t(row_bytes), ctypes.c_size_t(row_bytes),
+                                _ptr(idx), int(idx.shape[0]), _ptr(out))
+    return out
+
+
+def gather_kv(kv, idx_kv):
+    """KVCompress gather: kv [L,Hkv,d], idx_kv [Hkv,b] -> [Hkv,b,d] with
+    out[g,t] = kv[idx_kv[g,t], g]."""
+    kv = np.ascontiguousarray(kv)
+    L, Hkv, d = kv.shape
+    idx_kv = np.ascontiguousarray(idx_kv, dtype=np.int32)
+    if idx_kv.size and (idx_kv.min() < 0 or idx_kv.max() >= L):
+        raise IndexError("gather index out of range")
+    b = idx_kv.shape[1]
+    out = np.empty((Hkv, b, d), dtype=kv.dtype)
+    lib = _lib("f32")
+    for g in range(Hkv):
+        src = kv[:, g, :]
+        base = ctypes.c_void_p(kv.ctypes.data + g * d * kv.itemsize)
+        lib.orc_gather_rows(base, ctypes.c_size_t(kv.strides[0]), ctypes.c_size_t(d * kv.itemsize),
+                            _ptr(idx_kv[g]), b, _ptr(out[g]))
+        del src
+    return out
+
+
+def compress_kv(q_win, k, v, budget, pool_kernel=7, pool_mode="max", scale=None, causal=True,
+                x=None, k_tsp=None, precision="f32", threads=None):
+    """One layer of Algorithm 1 for one sequence: KVCompress with `budget` kept tokens per
+    KV head and, when x and k_tsp are given, HiddenCompress keeping k_tsp rows."""
+    W = q_win.shape[0]
+    sc = score_window(q_win, k, pool_kernel, pool_mode, scale, causal, precision, threads)
+    sg32 = sc["scores_group"].astype(np.float32)
+    idx_kv = np.stack([select_topk(sg32[g], W, budget) for g in range(k.shape[1])])
+    out = dict(sc)
+    out["idx_kv"] = idx_kv
+    out["k_out"] = gather_kv(k, idx_kv)
+    out["v_out"] = gather_kv(v, idx_kv)
+    if x is not None and k_tsp is not None:
+        idx_tsp = select_topk(sc["scores_tsp"].astype(np.float32), W, k_tsp)
+        out["idx_tsp"] = idx_tsp
+        out["x_out"] = gather_rows(x, idx_tsp)
+    return out

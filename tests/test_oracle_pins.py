@@ -1,0 +1,353 @@
+"""Pins for the CPU oracle: closed forms, library routines, brute force and invariants.
+
+None of these re-type the oracle's own loops: each compares it with something fixed by the
+mathematics (a closed form), by a library routine it must reduce to (torch CPU softmax,
+pooling, sort, index_select), or by exhaustive enumeration on tiny inputs.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_01068_amd import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "paper_identities.txt")
+
+
+def _gold():
+    out = {}
+    for line in open(GOLD):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, val, _ = [t.strip() for t in line.split("|", 2)]
+        out[name] = val
+    return out
+
+
+def _rand_bf16(rng, shape, scale=1.0):
+    return wl.f32_to_bf16_bits((scale * rng.standard_normal(shape)).astype(np.float32))
+
+
+def _torch_scores(q_win, k, pool_kernel, pool_mode, causal=True, scale=None):
+    """The whole scoring chain built from torch CPU library ops in fp64."""
+    q = torch.from_numpy(wl.bf16_bits_to_f32(q_win)).double()  # [W,Hq,d]
+    kk = torch.from_numpy(wl.bf16_bits_to_f32(k)).double()     # [L,Hkv,d]
+    W, Hq, d = q.shape
+    L, Hkv, _ = kk.shape
+    G, P = Hq // Hkv, L - W
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    kh = kk.repeat_interleave(G, dim=1)                        # head h uses KV head h // G
+    logits = torch.einsum("whc,lhc->hwl", q, kh) * scale       # [Hq,W,L]
+    if causal:
+        pos_q = torch.arange(P, L).view(1, W, 1)
+        pos_k = torch.arange(L).view(1, 1, L)
+        logits = logits.masked_fill(pos_k > pos_q, float("-inf"))
+    att = torch.softmax(logits, dim=-1)
+    s = att.sum(dim=1)[:, :P]                                  # [Hq,P]
+    r = pool_kernel // 2
+    if pool_mode == "max":
+        p = torch.nn.functional.max_pool1d(s.unsqueeze(0), pool_kernel, stride=1, padding=r).squeeze(0)
+    else:
+        p = torch.nn.functional.avg_pool1d(s.unsqueeze(0), pool_kernel, stride=1, padding=r,
+                                           count_include_pad=True).squeeze(0)
+    sg = p.view(Hkv, G, P).mean(dim=1)
+    st = p.mean(dim=0)
+    return s.numpy(), p.numpy(), sg.numpy(), st.numpy()
+
+
+# ----------------------------------------------------------------------------- scoring
+
+@pytest.mark.parametrize("prec,tol", [("f32", 2e-5), ("f64", 1e-12)])
+def test_single_row_is_textbook_softmax(prec, tol):
+    # Hq=Hkv=1, W=1, kernel 1: the score of prefix token j is softmax(q.K^T/sqrt(d))[j] over all L keys.
+    rng = np.random.default_rng(1)
+    L, d = 97, 32
+    q = _rand_bf16(rng, (1, 1, d))
+    k = _rand_bf16(rng, (L, 1, d))
+    sc = oracle.score_window(q, k, pool_kernel=1, pool_mode="max", precision=prec)
+    logits = torch.from_numpy(wl.bf16_bits_to_f32(k)[:, 0, :]).double() @ \
+        torch.from_numpy(wl.bf16_bits_to_f32(q)[0, 0]).double() / math.sqrt(d)
+    ref = torch.softmax(logits, dim=0)[: L - 1].numpy()
+    for name in ("s_head", "p_head", "scores_group"):
+        np.testing.assert_allclose(sc[name][0], ref, rtol=tol, atol=0)
+    np.testing.assert_allclose(sc["scores_tsp"], ref, rtol=tol, atol=0)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_equal_keys_closed_form(causal):
+    # All keys equal => every visible key gets 1/(number visible): causal row w sees P+w+1 keys.
+    W, Hq, Hkv, d, L = 8, 4, 2, 16, 40
+    rng = np.random.default_rng(2)
+    q = _rand_bf16(rng, (W, Hq, d))
+    k = np.zeros((L, Hkv, d), np.uint16)
+    P = L - W
+    s = oracle.window_attention(q, k, causal=causal, precision="f64")
+    expect = sum(1.0 / (P + w + 1) for w in range(W)) if causal else W / L
+    np.testing.assert_allclose(s, expect, rtol=1e-13)
+    s32 = oracle.window_attention(q, k, causal=causal, precision="f32")
+    np.testing.assert_allclose(s32, expect, rtol=1e-6)
+
+
+def test_causal_corner_by_hand():
+    # L = W+1: one prefix token; window row w sees exactly w+2 keys.
+    W, d = 8, 8
+    q = _rand_bf16(np.random.default_rng(3), (W, 1, d))
+    k = np.zeros((W + 1, 1, d), np.uint16)
+    s = oracle.window_attention(q, k, precision="f64")
+    assert s.shape == (1, 1)
+    np.testing.assert_allclose(s[0, 0], sum(1.0 / (w + 2) for w in range(W)), rtol=1e-14)
+
+
+@pytest.mark.parametrize("pool_mode", ["max", "avg"])
+@pytest.mark.parametrize("causal", [True, False])
+def test_scoring_chain_matches_library_ops(pool_mode, causal):
+    rng = np.random.default_rng(4)
+    W, Hq, Hkv, d, L = 8, 8, 2, 32, 150
+    q = _rand_bf16(rng, (W, Hq, d), 1.5)
+    k = _rand_bf16(rng, (L, Hkv, d), 1.5)
+    s, p, sg, st = _torch_scores(q, k, 7, pool_mode, causal)
+    o64 = oracle.score_window(q, k, 7, pool_mode, causal=causal, precision="f64")
+    np.testing.assert_allclose(o64["s_head"], s, rtol=1e-11)
+    np.testing.assert_allclose(o64["p_head"], p, rtol=1e-11)
+    np.testing.assert_allclose(o64["scores_group"], sg, rtol=1e-11)
+    np.testing.assert_allclose(o64["scores_tsp"], st, rtol=1e-11)
+    o32 = oracle.score_window(q, k, 7, pool_mode, causal=causal, precision="f32")
+    np.testing.assert_allclose(o32["scores_group"], sg, rtol=3e-5)
+    np.testing.assert_allclose(o32["scores_tsp"], st, rtol=3e-5)
+
+
+def test_group_map_is_contiguous_and_scale_is_used():
+    # A key aligned with one head's queries must raise that head's group only; a custom
+    # softmax scale must change the result the way the library chain says.
+    rng = np.random.default_rng(5)
+    W, Hq, Hkv, d, L = 4, 6, 3, 16, 60
+    q = _rand_bf16(rng, (W, Hq, d))
+    k = _rand_bf16(rng, (L, Hkv, d))
+    for scale in (None, 0.05, 1.0):
+        _, _, sg, st = _torch_scores(q, k, 3, "max", True, scale)
+        o = oracle.score_window(q, k, 3, "max", scale=scale, precision="f64")
+        np.testing.assert_allclose(o["scores_group"], sg, rtol=1e-11)
+        np.testing.assert_allclose(o["scores_tsp"], st, rtol=1e-11)
+
+
+def test_attention_mass_invariant():
+    # Each window row is a probability vector over the keys it sees, so prefix mass plus
+    # window-column mass equals W for every head.  Window-column mass comes from torch.
+    rng = np.random.default_rng(6)
+    W, Hq, Hkv, d, L = 8, 4, 1, 16, 64
+    q = _rand_bf16(rng, (W, Hq, d))
+    k = _rand_bf16(rng, (L, Hkv, d))
+    s = oracle.window_attention(q, k, precision="f64")
+    qf = torch.from_numpy(wl.bf16_bits_to_f32(q)).double()
+    kf = torch.from_numpy(wl.bf16_bits_to_f32(k)).double()[:, 0]
+    P = L - W
+    for h in range(Hq):
+        mass_win = 0.0
+        for w in range(W):
+            lg = kf[: P + w + 1] @ qf[w, h] / math.sqrt(d)
+            mass_win += torch.softmax(lg, 0)[P:].sum().item()
+        assert abs(s[h].sum() + mass_win - W) < 1e-12
+
+
+def test_fp32_oracle_rounding_is_far_below_tolerance():
+    s = wl.make_sequence(11, 1024, n_heavy=16, with_v=False, with_x=False)
+    for mode in ("max", "avg"):
+        a = oracle.score_window(s["q_win"], s["k"], 7, mode, precision="f32")
+        b = oracle.score_window(s["q_win"], s["k"], 7, mode, precision="f64")
+        for name in ("scores_group", "scores_tsp"):
+            rel = np.abs(a[name] - b[name]) / b[name]
+            assert rel.max() < 2e-5
+
+
+# ----------------------------------------------------------------------------- pooling / means
+
+@pytest.mark.parametrize("kernel", [1, 3, 7, 9])
+@pytest.mark.parametrize("P", [1, 2, 5, 64])
+def test_pooling_matches_library(kernel, P):
+    rng = np.random.default_rng(7)
+    s = rng.random((3, P))
+    t = torch.from_numpy(s).unsqueeze(0)
+    r = kernel // 2
+    mx = torch.nn.functional.max_pool1d(t, kernel, stride=1, padding=r).squeeze(0).numpy()
+    av = torch.nn.functional.avg_pool1d(t, kernel, stride=1, padding=r, count_include_pad=True).squeeze(0).numpy()
+    np.testing.assert_allclose(oracle.pool_rows(s, kernel, "max", "f64"), mx, rtol=0, atol=0)
+    np.testing.assert_allclose(oracle.pool_rows(s, kernel, "avg", "f64"), av, rtol=1e-14)
+    if kernel == 1:
+        np.testing.assert_array_equal(oracle.pool_rows(s, 1, "avg", "f64"), s)
+
+
+def test_pooling_invariants():
+    rng = np.random.default_rng(8)
+    s = rng.random((2, 200)).astype(np.float32)
+    mx = oracle.pool_rows(s, 7, "max")
+    assert (mx >= s).all()
+    # a single spike is replicated to exactly the 7 neighbours (exact ties)
+    z = np.zeros((1, 50), np.float32)
+    z[0, 20] = 1.0
+    m = oracle.pool_rows(z, 7, "max")[0]
+    assert (m[17:24] == 1.0).all() and m[:17].sum() == 0 and m[24:].sum() == 0
+    a = oracle.pool_rows(z, 7, "avg", "f64")[0]
+    np.testing.assert_allclose(a[17:24], 1 / 7, rtol=1e-15)
+    # avg pooling keeps interior mass: every input is counted 7 times / 7
+    inner = np.zeros((1, 100))
+    inner[0, 10:90] = rng.random(80)
+    np.testing.assert_allclose(oracle.pool_rows(inner, 7, "avg", "f64").sum(), inner.sum(), rtol=1e-13)
+
+
+def test_head_means_library_and_consistency():
+    rng = np.random.default_rng(9)
+    p = rng.random((12, 33))
+    sg, st = oracle.head_means(p, 3, "f64")
+    np.testing.assert_allclose(sg, p.reshape(3, 4, 33).mean(1), rtol=1e-14)
+    np.testing.assert_allclose(st, p.mean(0), rtol=1e-14)
+    np.testing.assert_allclose(st, sg.mean(0), rtol=1e-14)  # Eq. 2 == mean of the group means
+    perm = np.concatenate([np.array([1, 0, 3, 2]) + 4 * g for g in range(3)])
+    sg2, _ = oracle.head_means(p[perm], 3, "f64")
+    np.testing.assert_allclose(sg2, sg, rtol=1e-14)
+
+
+# ----------------------------------------------------------------------------- top-k
+
+def _brute_force(scores, kp):
+    """Lexicographically smallest subset of size kp in which every kept score >= every
+    dropped score, found by enumerating all subsets."""
+    P = len(scores)
+    for sub in itertools.combinations(range(P), kp):  # lexicographic order
+        kept = set(sub)
+        lo = min((scores[i] for i in sub), default=math.inf)
+        hi = max((scores[i] for i in range(P) if i not in kept), default=-math.inf)
+        if lo >= hi:
+            return list(sub)
+    raise AssertionError("no admissible subset")
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topk_brute_force_tiny(seed):
+    rng = np.random.default_rng(100 + seed)
+    W = 3
+    for P in (1, 2, 5, 9, 12):
+        # few distinct values => many exact ties
+        scores = rng.integers(0, 4, size=P).astype(np.float32) / 8
+        for kp in range(0, P + 1):
+            got = oracle.select_topk(scores, W, kp + W)
+            want = _brute_force(scores.tolist(), kp) + list(range(P, P + W))
+            assert got.tolist() == want, (P, kp, scores)
+
+
+def test_topk_brute_force_L64():
+    rng = np.random.default_rng(42)
+    P, W = 56, 8  # L = 64
+    scores = (rng.integers(0, 30, size=P) / 64).astype(np.float32)
+    for kp in (0, 1, 2, 3, 53, 54, 55, 56):  # C(56, kp) small enough to enumerate
+        got = oracle.select_topk(scores, W, kp + W)
+        want = _brute_force(scores.tolist(), kp) + list(range(P, P + W))
+        assert got.tolist() == want
+
+
+def test_topk_invariants_and_library_sort():
+    P, W = 5000, 8
+    scores = wl.random_scores(3, 1, P, ties=0.3)[0]
+    prev = None
+    for k in (8, 9, 100, 1000, 2500, 5008):
+        idx = oracle.select_topk(scores, W, k)
+        assert len(idx) == k and (np.diff(idx) > 0).all()
+        assert idx[-W:].tolist() == list(range(P, P + W))
+        kept = np.zeros(P, bool)
+        kept[idx[:-W]] = True
+        if kept.any() and (~kept).any():
+            assert scores[kept].min() >= scores[~kept].max()
+            tau = scores[kept].min()
+            # among ties at the threshold the kept ones come first
+            eq = np.nonzero(scores == tau)[0]
+            flags = kept[eq]
+            assert not (np.diff(flags.astype(int)) > 0).any()
+        if prev is not None:
+            assert set(prev[:-W].tolist()) <= set(idx[:-W].tolist())  # nested
+        prev = idx
+    # stable library sort on (-score) breaks ties to the lower index too
+    order = torch.sort(torch.from_numpy(-scores), stable=True).indices.numpy()
+    for k in (50, 2500):
+        want = np.sort(order[: k - W])
+        np.testing.assert_array_equal(oracle.select_topk(scores, W, k)[:-W], want)
+
+
+def test_topk_degenerate():
+    W = 8
+    flat = np.full(100, 0.25, np.float32)
+    assert oracle.select_topk(flat, W, 30).tolist() == list(range(22)) + list(range(100, 108))
+    assert oracle.select_topk(flat, W, 108).tolist() == list(range(108))  # k = L is the identity
+    assert oracle.select_topk(flat, W, 8).tolist() == list(range(100, 108))
+    assert oracle.select_topk(np.zeros(0, np.float32), W, 8).tolist() == list(range(8))
+    with pytest.raises(ValueError):
+        oracle.select_topk(flat, W, 7)
+    with pytest.raises(ValueError):
+        oracle.select_topk(flat, W, 109)
+
+
+# ----------------------------------------------------------------------------- gathers / chain
+
+def test_gather_matches_library_and_composes():
+    rng = np.random.default_rng(12)
+    x = rng.integers(0, 65536, size=(300, 24), dtype=np.uint16)
+    i1 = np.sort(rng.choice(300, 120, replace=False)).astype(np.int32)
+    i2 = np.sort(rng.choice(120, 40, replace=False)).astype(np.int32)
+    g1 = oracle.gather_rows(x, i1)
+    ref = torch.index_select(torch.from_numpy(x.astype(np.int32)), 0, torch.from_numpy(i1).long()).numpy()
+    np.testing.assert_array_equal(g1, ref.astype(np.uint16))
+    np.testing.assert_array_equal(oracle.gather_rows(x, np.arange(300)), x)
+    np.testing.assert_array_equal(oracle.gather_rows(g1, i2), oracle.gather_rows(x, i1[i2]))
+    kv = rng.integers(0, 65536, size=(50, 3, 8), dtype=np.uint16)
+    idx = np.stack([np.sort(rng.choice(50, 7, replace=False)) for _ in range(3)]).astype(np.int32)
+    out = oracle.gather_kv(kv, idx)
+    for g in range(3):
+        np.testing.assert_array_equal(out[g], kv[idx[g], g, :])
+    with pytest.raises(IndexError):
+        oracle.gather_rows(x, np.array([300], np.int32))
+
+
+def test_compress_kv_composition_and_heavy_recall():
+    s = wl.make_sequence(5, 1024, n_heavy=32)
+    out = oracle.compress_kv(s["q_win"], s["k"], s["v"], 128, 7, "max", x=s["x"], k_tsp=256)
+    assert out["idx_kv"].shape == (8, 128) and out["idx_tsp"].shape == (256,)
+    for g in range(8):
+        np.testing.assert_array_equal(out["k_out"][g], s["k"][out["idx_kv"][g], g])
+        np.testing.assert_array_equal(out["v_out"][g], s["v"][out["idx_kv"][g], g])
+    np.testing.assert_array_equal(out["x_out"], s["x"][out["idx_tsp"]])
+    # planted heavy positions are far more likely to be kept than chance (sanity, not a gate)
+    recall = np.isin(s["heavy"], out["idx_tsp"]).mean()
+    assert recall > 0.8
+
+
+def test_paper_identities():
+    g = _gold()
+    n_layers, tsp_layer, rate = int(g["n_layers_llama"]), int(g["tsp_layer_llama"]), float(g["tsp_rate"])
+    # Algorithm 1: layers 0..L_TSP see the full context, later layers the kept fraction.
+    full = tsp_layer + 1
+    compute_rate = (full * 1.0 + (n_layers - full) * rate) / n_layers
+    assert abs(compute_rate - float(g["prefill_compute_rate"])) < 1e-12
+    L = 32768
+    k = wl.round_half_up(rate * L)
+    assert k == 6554 and wl.round_half_up(0.2 * 131072) == 26214 and wl.round_half_up(0.1 * 131072) == 13107
+    assert full * L + (n_layers - full) * k == 16 * 32768 + 16 * 6554
+    # printed as 0.38 %; 512 / 131072 is 0.39 %: arithmetic sanity only
+    assert abs(100 * 512 / 131072 - float(g["topk_fraction_512_of_128k_percent"])) < 0.015
+    assert int(g["window_size"]) == 8 and int(g["pool_kernel"]) == 7 and g["pool_type"] == "max"
+
+
+def test_workload_recipe():
+    a = wl.make_sequence(0, 512, n_heavy=8)
+    b = wl.make_sequence(0, 512, n_heavy=8)
+    for name in ("q_win", "k", "v", "x", "heavy"):
+        np.testing.assert_array_equal(a[name], b[name])
+    assert a["heavy"].max() < 512 - 8 and len(np.unique(a["heavy"])) == 8
+    kf = wl.bf16_bits_to_f32(a["k"])
+    assert abs(kf.std() - 1.0) < 0.05
+    # bf16 rounding is round-to-nearest-even and matches torch's
+    f = np.random.default_rng(0).standard_normal(10000).astype(np.float32)
+    ref = torch.from_numpy(f).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(wl.f32_to_bf16_bits(f), ref)
+    assert wl.algorithmic_bytes(32768, 6554, 2048) == 193874576
