@@ -1,0 +1,152 @@
+/*
+ * libfastkv_select: token-importance selection of FastKV (arXiv 2502.01068) on MI355X (gfx950).
+ *
+ * What it computes (paper notation; L = N_I tokens, W = N_obs window queries, P = L - W):
+ *   score   S^{l,h}_i = Pooling( sum_{w<W} Att_l[h, P+w, i+m] )            Sec. 4.2, Eq. 1
+ *           group score = mean of S^{l,h} over the heads of a KV group     App. B.1, KVCompress
+ *           TSP score   = mean of S^{l,h} over all H heads                 Sec. 4.2, Eq. 2
+ *   select  indices of the top-ranked prefix tokens, window tokens always
+ *           kept and merged in                                             Sec. 4.2
+ *   gather  hidden rows (HiddenCompress) and per-KV-head K/V rows
+ *           (KVCompress) of the kept tokens                                App. B.1, Algorithm 1
+ *
+ * Conventions for every call
+ *   - C ABI, no exceptions.  Return value: FKV_OK (0) or a negative fkv_status.
+ *   - Pointers named q_win, k, v, x, scores*, idx*, *_out are DEVICE pointers, 16-byte
+ *     aligned, owned by the caller; the library never frees or keeps them.  Inputs are
+ *     read-only and must not alias outputs.
+ *   - fkv_shape and every *_per_seq / cu_seqlens array are HOST memory, read during the
+ *     call only.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream).  Calls never synchronise, never allocate, and validate every argument on
+ *     the host before the first launch, so a rejected call has no effect.
+ *   - Two calls that share a context must be ordered on one stream (they share the
+ *     context's workspace).
+ *   - bf16 tensors are raw 16-bit patterns.  Scores are fp32, indices int32.
+ *
+ * Tensor layouts (B = n_seq sequences packed along tokens, T_b = cu_seqlens[b], sum L = T_B)
+ *   q_win        [B][W][Hq][d]      bf16   queries of the last W positions of each sequence
+ *   k, v         [sum L][Hkv][d]    bf16   token-major
+ *   x            [sum L][row_bytes]        hidden states (row_bytes = 2*hidden for bf16)
+ *   scores_group [Hkv][sum P]       fp32   sequence b starts at column T_b - b*W
+ *   scores_tsp   [sum P]            fp32
+ *   idx (1 row set)  [n_rows][sum k]  int32  sequence-local token positions, ascending,
+ *                                            sequence b starts at column sum_{b'<b} k_b'
+ *   k_out, v_out [Hkv][sum budget][d] bf16
+ *   x_out        [sum k][row_bytes]
+ *
+ * Supported shapes: head_dim = 128; 1 <= W <= 8; Hq = G*Hkv with 1 <= G <= 4;
+ * 1 <= Hkv <= 8; odd pool_kernel <= 31; B <= FKV_MAX_SEQS.  Anything else returns
+ * FKV_EUNSUPPORTED.
+ */
+#ifndef FASTKV_SELECT_H
+#define FASTKV_SELECT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FKV_MAX_SEQS 64
+
+typedef enum {
+  FKV_OK = 0,
+  FKV_EINVAL = -1,       /* a size, count or flag is out of range */
+  FKV_ENULL = -2,        /* a required pointer is NULL */
+  FKV_EALIGN = -3,       /* a device pointer or row size is not a multiple of 16 bytes */
+  FKV_EUNSUPPORTED = -4, /* valid problem, shape outside what the kernels cover */
+  FKV_EWORKSPACE = -5,   /* problem larger than the context was created for */
+  FKV_EHIP = -6          /* a HIP runtime call failed; see fkv_last_hip_error */
+} fkv_status;
+
+typedef enum { FKV_POOL_AVG = 0, FKV_POOL_MAX = 1 } fkv_pool_t;
+
+/* Problem description (host struct). */
+typedef struct fkv_shape {
+  int32_t n_seq;             /* B >= 1 */
+  const int32_t *cu_seqlens; /* host [B+1], cu[0] = 0, strictly increasing; may be NULL when B == 1 */
+  int32_t L;                 /* tokens of the single sequence when cu_seqlens == NULL */
+  int32_t n_q_heads;         /* Hq */
+  int32_t n_kv_heads;        /* Hkv; query head h reads KV head h / (Hq/Hkv) */
+  int32_t head_dim;          /* d */
+  int32_t window;            /* W = N_obs (Sec. 5.1 uses 8) */
+  int32_t pool_kernel;       /* odd; Sec. 5.1 uses 7 */
+  int32_t pool_mode;         /* fkv_pool_t; App. D.4 names max pooling */
+  float softmax_scale;       /* 0 means 1/sqrt(d) */
+  int32_t causal;            /* 1: window query w sees keys j <= P + w; 0: all L keys */
+} fkv_shape;
+
+typedef struct fkv_ctx fkv_ctx;
+
+/* Library version as major*10000 + minor*100 + patch. */
+int fkv_version(void);
+const char *fkv_strerror(int status);
+/* hipError_t of the last failed HIP call on this thread (0 if none). */
+int fkv_last_hip_error(void);
+
+/* Host-only checks, usable without a GPU.  fkv_check_shape validates a shape;
+ * fkv_check_counts validates a per-sequence keep count array (W <= count_b <= L_b). */
+int fkv_check_shape(const fkv_shape *shape);
+int fkv_check_counts(const fkv_shape *shape, const int32_t *count_per_seq);
+
+/* Device workspace a context needs for problems of up to max_total_tokens tokens in up to
+ * max_seqs sequences (Hkv <= 8). */
+size_t fkv_workspace_bytes(int64_t max_total_tokens, int32_t max_seqs);
+
+/* Create a context on HIP device `device`; allocates the workspace once (the only
+ * allocation the library ever makes).  fkv_destroy frees it; the caller must have
+ * synchronised the streams that used it. */
+int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_seqs);
+int fkv_destroy(fkv_ctx *ctx);
+
+/* score_window(Q_win, K) -> per-token scores (Eq. 1, Eq. 2, App. B.1 group mean).
+ * scores_group is required (unless no sequence has a prefix token); scores_tsp may be NULL. */
+int fkv_score_window(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k,
+                     float *scores_group, float *scores_tsp, void *stream);
+
+/* select_topk(scores, k) -> ascending kept indices (Sec. 4.2).  `scores` holds n_rows rows
+ * laid out like scores_group (row stride = sum P floats).  For each row and sequence the
+ * k_b - W largest prefix scores are kept (equal scores: lower index first) and the W window
+ * positions P_b .. L_b-1 are appended, so exactly k_b indices come out.  Requires
+ * W <= k_b <= L_b.  NaN scores are outside the contract. */
+int fkv_select_topk(fkv_ctx *ctx, const fkv_shape *shape, const float *scores, int32_t n_rows,
+                    const int32_t *k_per_seq, int32_t *idx_out, void *stream);
+
+/* gather_rows(X, idx): out[o_b + t][:] = x[T_b + idx[o_b + t]][:] for t < k_b, where
+ * o_b = sum_{b'<b} k_b' (HiddenCompress, App. B.1).  Rows are copied bit for bit.
+ * Indices must lie in [0, L_b); they are not checked on the device. */
+int fkv_gather_rows(fkv_ctx *ctx, const fkv_shape *shape, const void *x, size_t row_bytes,
+                    const int32_t *idx, const int32_t *k_per_seq, void *out, void *stream);
+
+/* Per-KV-head gather of KVCompress (App. B.1): for g < Hkv,
+ * k_out[g][o_b + t][:] = k[T_b + idx_kv[g][o_b + t]][g][:], same for v.  v / v_out may both
+ * be NULL to gather K only. */
+int fkv_gather_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const void *v,
+                  const int32_t *idx_kv, const int32_t *budget_per_seq, void *k_out, void *v_out,
+                  void *stream);
+
+/* compress_kv(K, V, budget): one layer's selection of Algorithm 1 in one call: score once,
+ * select budget_b tokens per KV head, gather K/V; and, when x != NULL, also the TSP leg
+ * (HiddenCompress): select k_tsp_b tokens on the all-head score and gather hidden rows.
+ * idx_kv [Hkv][sum budget] and idx_tsp [sum k_tsp] are outputs.  x, k_tsp_per_seq, x_out,
+ * idx_tsp are either all given or all NULL (x_row_bytes ignored then). */
+int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k,
+                    const void *v, const int32_t *budget_per_seq, void *k_out, void *v_out,
+                    int32_t *idx_kv, const void *x, size_t x_row_bytes,
+                    const int32_t *k_tsp_per_seq, void *x_out, int32_t *idx_tsp, void *stream);
+
+/* Per-kernel device timing for benchmarks.  While enabled, every launch is bracketed by
+ * HIP events on the caller's stream.  fkv_profile_read synchronises those events, writes
+ * the accumulated milliseconds and launch counts of kernel ids 0 .. n-1 (n =
+ * fkv_profile_kernels()) and clears the accumulators.  Not for use under graph capture. */
+int fkv_profile_kernels(void);
+const char *fkv_profile_kernel_name(int id);
+int fkv_profile_enable(fkv_ctx *ctx, int on);
+int fkv_profile_read(fkv_ctx *ctx, float *ms_out, int32_t *launches_out, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTKV_SELECT_H */

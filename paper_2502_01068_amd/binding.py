@@ -1,0 +1,257 @@
+"""ctypes binding of libfastkv_select (argument marshalling only; every step runs in the HIP kernels).
+
+Functions carry the names of the C ABI in ``include/fastkv_select.h``.  torch is used for
+device memory and the current stream; tensors must live on the context's GPU.  A missing
+library is an error: there is no fallback path.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfastkv_select.so")
+
+FKV_MAX_SEQS = 64
+FKV_OK, FKV_EINVAL, FKV_ENULL, FKV_EALIGN, FKV_EUNSUPPORTED, FKV_EWORKSPACE, FKV_EHIP = 0, -1, -2, -3, -4, -5, -6
+FKV_POOL_AVG, FKV_POOL_MAX = 0, 1
+_POOL = {"avg": FKV_POOL_AVG, "max": FKV_POOL_MAX, FKV_POOL_AVG: FKV_POOL_AVG, FKV_POOL_MAX: FKV_POOL_MAX}
+
+EXPORTS = [
+    "fkv_version", "fkv_strerror", "fkv_last_hip_error", "fkv_check_shape", "fkv_check_counts",
+    "fkv_workspace_bytes", "fkv_create", "fkv_destroy", "fkv_score_window", "fkv_select_topk",
+    "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
+    "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read",
+]
+
+
+class FkvShape(ctypes.Structure):
+    _fields_ = [("n_seq", ctypes.c_int32), ("cu_seqlens", ctypes.POINTER(ctypes.c_int32)), ("L", ctypes.c_int32),
+                ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("window", ctypes.c_int32), ("pool_kernel", ctypes.c_int32), ("pool_mode", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float), ("causal", ctypes.c_int32)]
+
+
+class FkvError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = load().fkv_strerror(status).decode()
+        if status == FKV_EHIP:
+            msg += " [hipError %d]" % load().fkv_last_hip_error()
+        super().__init__("%s: %s (%d)" % (where, msg, status))
+
+
+_lib = None
+
+
+def load():
+    """Open libfastkv_select.so (built in-tree by build.py) and declare its signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError("libfastkv_select.so is not built: run `python -m paper_2502_01068_amd.build` "
+                                "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    shp, pi32 = ctypes.POINTER(FkvShape), ctypes.POINTER(ctypes.c_int32)
+    lib.fkv_version.restype = ctypes.c_int
+    lib.fkv_strerror.restype = ctypes.c_char_p
+    lib.fkv_strerror.argtypes = [ctypes.c_int]
+    lib.fkv_last_hip_error.restype = ctypes.c_int
+    lib.fkv_check_shape.argtypes = [shp]
+    lib.fkv_check_counts.argtypes = [shp, pi32]
+    lib.fkv_workspace_bytes.restype = sz
+    lib.fkv_workspace_bytes.argtypes = [i64, i32]
+    lib.fkv_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i32]
+    lib.fkv_destroy.argtypes = [vp]
+    lib.fkv_score_window.argtypes = [vp, shp, vp, vp, vp, vp, vp]
+    lib.fkv_select_topk.argtypes = [vp, shp, vp, i32, pi32, vp, vp]
+    lib.fkv_gather_rows.argtypes = [vp, shp, vp, sz, vp, pi32, vp, vp]
+    lib.fkv_gather_kv.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
+    lib.fkv_compress_kv.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp, vp, sz, pi32, vp, vp, vp]
+    lib.fkv_profile_kernels.restype = ctypes.c_int
+    lib.fkv_profile_kernel_name.restype = ctypes.c_char_p
+    lib.fkv_profile_kernel_name.argtypes = [ctypes.c_int]
+    lib.fkv_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.fkv_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), pi32, i32]
+    for name in EXPORTS:
+        getattr(lib, name)  # raises AttributeError if a declared symbol is missing
+    _lib = lib
+    return lib
+
+
+def _i32_array(values):
+    vals = [int(v) for v in values]
+    return (ctypes.c_int32 * len(vals))(*vals)
+
+
+def make_shape(lengths, n_q_heads=32, n_kv_heads=8, head_dim=128, window=8, pool_kernel=7, pool_mode="max",
+               softmax_scale=0.0, causal=True):
+    """Build the host descriptor.  `lengths` is an int (single sequence) or a list of
+    per-sequence token counts.  Returns (FkvShape, keepalive) - keep both alive for the call."""
+    s = FkvShape()
+    if isinstance(lengths, int):
+        lengths = [lengths]
+    cu = [0]
+    for n in lengths:
+        cu.append(cu[-1] + int(n))
+    arr = _i32_array(cu)
+    s.n_seq = len(lengths)
+    s.cu_seqlens = ctypes.cast(arr, ctypes.POINTER(ctypes.c_int32))
+    s.L = int(lengths[0])
+    s.n_q_heads, s.n_kv_heads, s.head_dim = int(n_q_heads), int(n_kv_heads), int(head_dim)
+    s.window, s.pool_kernel, s.pool_mode = int(window), int(pool_kernel), _POOL[pool_mode]
+    s.softmax_scale, s.causal = float(softmax_scale), int(bool(causal))
+    s._keep = arr
+    s._lengths = [int(n) for n in lengths]
+    return s
+
+
+def _check(status, where):
+    if status != FKV_OK:
+        raise FkvError(status, where)
+
+
+def _dev_ptr(t, name, dtypes=None, allow_none=False):
+    if t is None:
+        if allow_none:
+            return None
+        raise ValueError("%s is required" % name)
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError("%s must be a GPU tensor" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtypes is not None and t.dtype not in dtypes:
+        raise ValueError("%s has dtype %s, expected one of %s" % (name, t.dtype, dtypes))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+_BF16 = (torch.bfloat16, torch.int16, torch.uint16)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _counts(shape, counts):
+    if isinstance(counts, int):
+        counts = [counts] * shape.n_seq
+    counts = [int(c) for c in counts]
+    if len(counts) != shape.n_seq:
+        raise ValueError("need one count per sequence")
+    return counts, _i32_array(counts)
+
+
+class Context:
+    """Owns an fkv_ctx (device workspace sized for max_total_tokens / max_seqs)."""
+
+    def __init__(self, max_total_tokens, max_seqs=1, device=None):
+        lib = load()
+        if not torch.cuda.is_available():
+            raise RuntimeError("libfastkv_select needs a GPU; no CPU path exists")
+        self.device = torch.cuda.current_device() if device is None else int(device)
+        h = ctypes.c_void_p()
+        _check(lib.fkv_create(ctypes.byref(h), self.device, int(max_total_tokens), int(max_seqs)), "fkv_create")
+        self.handle = h
+        self.max_total_tokens = int(max_total_tokens)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            torch.cuda.synchronize(self.device)
+            load().fkv_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- the C ABI, same names -----------------------------------------------------------
+    def fkv_score_window(self, shape, q_win, k, scores_group=None, scores_tsp=None, want_tsp=True):
+        """-> (scores_group [Hkv, sum P] fp32, scores_tsp [sum P] fp32 or None)"""
+        total = sum(shape._lengths)
+        sum_p = total - shape.n_seq * shape.window
+        dev = k.device
+        if scores_group is None:
+            scores_group = torch.empty((shape.n_kv_heads, sum_p), dtype=torch.float32, device=dev)
+        if scores_tsp is None and want_tsp:
+            scores_tsp = torch.empty((sum_p,), dtype=torch.float32, device=dev)
+        _check(load().fkv_score_window(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
+                                       _dev_ptr(k, "k", _BF16), _dev_ptr(scores_group, "scores_group", (torch.float32,)),
+                                       _dev_ptr(scores_tsp, "scores_tsp", (torch.float32,), True), _stream()),
+               "fkv_score_window")
+        return scores_group, scores_tsp
+
+    def fkv_select_topk(self, shape, scores, k_per_seq, idx_out=None):
+        """scores [n_rows, sum P] (or [sum P]) -> idx [n_rows, sum k] int32"""
+        counts, arr = _counts(shape, k_per_seq)
+        n_rows = 1 if scores.dim() == 1 else scores.shape[0]
+        if idx_out is None:
+            idx_out = torch.empty((n_rows, sum(counts)), dtype=torch.int32, device=scores.device)
+        _check(load().fkv_select_topk(self.handle, ctypes.byref(shape), _dev_ptr(scores, "scores", (torch.float32,)),
+                                      n_rows, arr, _dev_ptr(idx_out, "idx_out", (torch.int32,)), _stream()),
+               "fkv_select_topk")
+        return idx_out
+
+    def fkv_gather_rows(self, shape, x, idx, k_per_seq, out=None):
+        """x [sum L, ...] -> out [sum k, ...] (rows copied bit for bit)"""
+        counts, arr = _counts(shape, k_per_seq)
+        row_bytes = x.stride(0) * x.element_size()
+        if out is None:
+            out = torch.empty((sum(counts),) + tuple(x.shape[1:]), dtype=x.dtype, device=x.device)
+        _check(load().fkv_gather_rows(self.handle, ctypes.byref(shape), _dev_ptr(x, "x"), row_bytes,
+                                      _dev_ptr(idx, "idx", (torch.int32,)), arr, _dev_ptr(out, "out"), _stream()),
+               "fkv_gather_rows")
+        return out
+
+    def fkv_gather_kv(self, shape, k, v, idx_kv, budget_per_seq, k_out=None, v_out=None):
+        counts, arr = _counts(shape, budget_per_seq)
+        tot = sum(counts)
+        if k_out is None:
+            k_out = torch.empty((shape.n_kv_heads, tot, shape.head_dim), dtype=k.dtype, device=k.device)
+        if v is not None and v_out is None:
+            v_out = torch.empty((shape.n_kv_heads, tot, shape.head_dim), dtype=v.dtype, device=v.device)
+        _check(load().fkv_gather_kv(self.handle, ctypes.byref(shape), _dev_ptr(k, "k", _BF16),
+                                    _dev_ptr(v, "v", _BF16, True), _dev_ptr(idx_kv, "idx_kv", (torch.int32,)), arr,
+                                    _dev_ptr(k_out, "k_out"), _dev_ptr(v_out, "v_out", None, True), _stream()),
+               "fkv_gather_kv")
+        return k_out, v_out
+
+    def fkv_compress_kv(self, shape, q_win, k, v, budget_per_seq, x=None, k_tsp_per_seq=None, out=None):
+        """One layer of Algorithm 1.  Returns dict(k_out, v_out, idx_kv[, x_out, idx_tsp]).
+        Pass `out` (a dict from a previous call) to reuse the output buffers."""
+        b_counts, b_arr = _counts(shape, budget_per_seq)
+        tsp = x is not None
+        if tsp:
+            t_counts, t_arr = _counts(shape, k_tsp_per_seq)
+        dev = k.device
+        if out is None:
+            out = {"k_out": torch.empty((shape.n_kv_heads, sum(b_counts), shape.head_dim), dtype=k.dtype, device=dev),
+                   "v_out": torch.empty((shape.n_kv_heads, sum(b_counts), shape.head_dim), dtype=v.dtype, device=dev),
+                   "idx_kv": torch.empty((shape.n_kv_heads, sum(b_counts)), dtype=torch.int32, device=dev)}
+            if tsp:
+                out["x_out"] = torch.empty((sum(t_counts),) + tuple(x.shape[1:]), dtype=x.dtype, device=dev)
+                out["idx_tsp"] = torch.empty((sum(t_counts),), dtype=torch.int32, device=dev)
+        row_bytes = x.stride(0) * x.element_size() if tsp else 0
+        _check(load().fkv_compress_kv(
+            self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16), _dev_ptr(k, "k", _BF16),
+            _dev_ptr(v, "v", _BF16), b_arr, _dev_ptr(out["k_out"], "k_out"), _dev_ptr(out["v_out"], "v_out"),
+            _dev_ptr(out["idx_kv"], "idx_kv", (torch.int32,)), _dev_ptr(x, "x", None, True), row_bytes,
+            t_arr if tsp else None, _dev_ptr(out.get("x_out"), "x_out", None, True),
+            _dev_ptr(out.get("idx_tsp"), "idx_tsp", (torch.int32,), True), _stream()), "fkv_compress_kv")
+        return out
+
+    # ---- timing facility -----------------------------------------------------------------
+    def fkv_profile_enable(self, on=True):
+        _check(load().fkv_profile_enable(self.handle, int(bool(on))), "fkv_profile_enable")
+
+    def fkv_profile_read(self):
+        """-> {kernel name: (total ms, launches)} since the last read (synchronises)."""
+        lib = load()
+        n = lib.fkv_profile_kernels()
+        ms = (ctypes.c_float * n)()
+        cnt = (ctypes.c_int32 * n)()
+        _check(lib.fkv_profile_read(self.handle, ms, cnt, n), "fkv_profile_read")
+        return {lib.fkv_profile_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}

@@ -1,0 +1,483 @@
+// C ABI of libfastkv_select: host-side validation, workspace carving and launch sequencing.
+// Every entry point validates on the host first, then only enqueues kernels on the caller's
+// stream; nothing here synchronises or allocates after fkv_create.
+#include <math.h>
+#include <new>
+#include <string.h>
+#include <vector>
+
+#include "fkv_internal.h"
+
+using namespace fkv;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct WsLayout {
+  size_t partial, rowstat, scores_group, scores_tsp, total;
+  int max_stat_blocks;
+};
+
+WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
+  WsLayout w{};
+  const int chunk = stats_chunk_tokens();
+  w.max_stat_blocks = (int)((max_tokens + chunk - 1) / chunk) + max_seqs;
+  size_t off = 0;
+  w.partial = off;      off += align_up((size_t)w.max_stat_blocks * kMaxKvHeads * kRowsPerGroup * sizeof(float2));
+  w.rowstat = off;      off += align_up((size_t)max_seqs * kMaxKvHeads * kRowsPerGroup * sizeof(float));
+  w.scores_group = off; off += align_up((size_t)max_tokens * kMaxKvHeads * sizeof(float));
+  w.scores_tsp = off;   off += align_up((size_t)max_tokens * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+struct EventPair { hipEvent_t a, b; int kid; };
+
+}  // namespace
+
+struct fkv_ctx {
+  int device;
+  int64_t max_tokens;
+  int32_t max_seqs;
+  WsLayout lay;
+  uint8_t *ws;
+  bool prof_on;
+  std::vector<EventPair> ev_pool;
+  size_t ev_used;
+  float ms_acc[KID_COUNT];
+  int32_t n_acc[KID_COUNT];
+};
+
+namespace {
+
+const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather"};
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return FKV_EHIP;
+}
+
+// Resolved view of a shape: per-sequence token offsets.
+struct Resolved {
+  int n_seq;
+  int cu[FKV_MAX_SEQS + 1];
+  int W, Hq, Hkv, G;
+  int64_t total, sum_p;
+};
+
+int resolve(const fkv_shape *s, Resolved *r) {
+  if (!s) return FKV_ENULL;
+  if (s->n_seq < 1) return FKV_EINVAL;
+  if (s->window < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->head_dim < 1) return FKV_EINVAL;
+  if (s->n_q_heads % s->n_kv_heads != 0) return FKV_EINVAL;
+  if (s->pool_kernel < 1 || (s->pool_kernel & 1) == 0) return FKV_EINVAL;
+  if (s->pool_mode != FKV_POOL_AVG && s->pool_mode != FKV_POOL_MAX) return FKV_EINVAL;
+  if (s->causal != 0 && s->causal != 1) return FKV_EINVAL;
+  if (!(s->softmax_scale >= 0.0f) || !isfinite(s->softmax_scale)) return FKV_EINVAL;
+  if (!s->cu_seqlens && s->n_seq != 1) return FKV_ENULL;
+  if (s->n_seq > FKV_MAX_SEQS) return FKV_EUNSUPPORTED;
+  if (s->head_dim != kHeadDim) return FKV_EUNSUPPORTED;
+  if (s->window > kMaxWindow) return FKV_EUNSUPPORTED;
+  if (s->n_kv_heads > kMaxKvHeads || s->n_q_heads / s->n_kv_heads > kMaxGroup) return FKV_EUNSUPPORTED;
+  if (s->pool_kernel > kMaxPoolKernel) return FKV_EUNSUPPORTED;
+  r->n_seq = s->n_seq;
+  if (s->cu_seqlens) {
+    if (s->cu_seqlens[0] != 0) return FKV_EINVAL;
+    for (int b = 0; b <= s->n_seq; ++b) r->cu[b] = s->cu_seqlens[b];
+  } else {
+    r->cu[0] = 0;
+    r->cu[1] = s->L;
+  }
+  for (int b = 0; b < r->n_seq; ++b)
+    if ((int64_t)r->cu[b + 1] - r->cu[b] < s->window) return FKV_EINVAL;  // also rejects non-monotone
+  r->W = s->window;
+  r->Hq = s->n_q_heads;
+  r->Hkv = s->n_kv_heads;
+  r->G = r->Hq / r->Hkv;
+  r->total = r->cu[r->n_seq];
+  r->sum_p = r->total - (int64_t)r->n_seq * r->W;
+  return FKV_OK;
+}
+
+int check_counts(const Resolved &r, const int32_t *cnt, int *off /*[n_seq+1]*/) {
+  if (!cnt) return FKV_ENULL;
+  int64_t acc = 0;
+  off[0] = 0;
+  for (int b = 0; b < r.n_seq; ++b) {
+    const int Lb = r.cu[b + 1] - r.cu[b];
+    if (cnt[b] < r.W || cnt[b] > Lb) return FKV_EINVAL;
+    acc += cnt[b];
+    if (acc > INT32_MAX) return FKV_EINVAL;
+    off[b + 1] = (int)acc;
+  }
+  return FKV_OK;
+}
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_ctx(const fkv_ctx *ctx, const Resolved &r) {
+  if (!ctx) return FKV_ENULL;
+  if (r.total > ctx->max_tokens || r.n_seq > ctx->max_seqs) return FKV_EWORKSPACE;
+  return FKV_OK;
+}
+
+// Launch bracket for the timing facility.
+struct Timed {
+  fkv_ctx *ctx;
+  hipStream_t s;
+  EventPair *ev;
+  Timed(fkv_ctx *c, hipStream_t st, int kid) : ctx(c), s(st), ev(nullptr) {
+    if (c->prof_on && c->ev_used < c->ev_pool.size()) {
+      ev = &c->ev_pool[c->ev_used++];
+      ev->kid = kid;
+      (void)hipEventRecord(ev->a, s);
+    }
+  }
+  ~Timed() {
+    if (ev) (void)hipEventRecord(ev->b, s);
+  }
+};
+
+void fill_map(const Resolved &r, SeqMap *m) {
+  m->n_seq = r.n_seq;
+  for (int b = 0; b <= r.n_seq; ++b) m->cu[b] = r.cu[b];
+}
+
+int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const void *q_win, const void *k,
+                  float *scores_group, float *scores_tsp, hipStream_t st) {
+  ScoreArgs a{};
+  a.q_win = static_cast<const uint16_t *>(q_win);
+  a.k = static_cast<const uint16_t *>(k);
+  a.partial = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.partial);
+  a.rowstat = reinterpret_cast<float *>(ctx->ws + ctx->lay.rowstat);
+  a.scores_group = scores_group;
+  a.scores_tsp = scores_tsp;
+  a.Hq = r.Hq; a.Hkv = r.Hkv; a.G = r.G; a.W = r.W;
+  const float scale = sh->softmax_scale > 0.f ? sh->softmax_scale : 1.0f / sqrtf((float)sh->head_dim);
+  a.scale_log2e = scale * 1.4426950408889634f;
+  a.causal = sh->causal;
+  a.pool_r = sh->pool_kernel / 2;
+  a.pool_mode = sh->pool_mode;
+  a.chunk = stats_chunk_tokens();
+  a.sum_p = r.sum_p;
+  fill_map(r, &a.map);
+
+  // pass 1: softmax statistics of every window row over all L keys
+  int nb = 0;
+  for (int b = 0; b < r.n_seq; ++b) {
+    a.map.blk[b] = nb;
+    nb += (r.cu[b + 1] - r.cu[b] + a.chunk - 1) / a.chunk;
+  }
+  a.map.blk[r.n_seq] = nb;
+  if (nb > ctx->lay.max_stat_blocks) return FKV_EWORKSPACE;
+  hipError_t e;
+  { Timed t(ctx, st, KID_STATS);   e = launch_stats(a, nb, st); }
+  if (e != hipSuccess) return hip_fail(e);
+  { Timed t(ctx, st, KID_COMBINE); e = launch_combine(a, st); }
+  if (e != hipSuccess) return hip_fail(e);
+
+  // pass 2: scores of the prefix tokens
+  const int tout = scores_tile_out(a.pool_r);
+  nb = 0;
+  for (int b = 0; b < r.n_seq; ++b) {
+    a.map.blk[b] = nb;
+    const int P = r.cu[b + 1] - r.cu[b] - r.W;
+    nb += (P + tout - 1) / tout;
+  }
+  a.map.blk[r.n_seq] = nb;
+  if (nb > 0) {
+    Timed t(ctx, st, KID_SCORES);
+    e = launch_scores(a, nb, st);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return FKV_OK;
+}
+
+void fill_rowset(SelectRowSet *rs, const float *scores, int64_t stride, int n_rows, int32_t *out,
+                 const int *off, int n_seq) {
+  rs->scores = scores;
+  rs->row_stride = stride;
+  rs->n_rows = n_rows;
+  rs->idx_out = out;
+  for (int b = 0; b <= n_seq; ++b) rs->cnt_off[b] = off[b];
+}
+
+void fill_job(GatherJob *j, const void *src, void *dst, const int32_t *idx, int64_t stride, int row_bytes,
+              int n_heads, const int *off, int n_seq) {
+  j->src = static_cast<const uint8_t *>(src);
+  j->dst = static_cast<uint8_t *>(dst);
+  j->idx = idx;
+  j->src_row_stride = stride;
+  j->row_bytes = row_bytes;
+  j->n_heads = n_heads;
+  j->total_rows = off[n_seq];
+  for (int b = 0; b <= n_seq; ++b) j->cnt_off[b] = off[b];
+}
+
+int enqueue_gather(fkv_ctx *ctx, GatherArgs &g, const Resolved &r, hipStream_t st) {
+  g.n_seq = r.n_seq;
+  for (int b = 0; b <= r.n_seq; ++b) g.cu[b] = r.cu[b];
+  int nb = 0;
+  for (int i = 0; i < g.n_jobs; ++i) {
+    g.job[i].blk0 = nb;
+    nb += gather_blocks(g.job[i]);
+  }
+  if (nb == 0) return FKV_OK;
+  Timed t(ctx, st, KID_GATHER);
+  const hipError_t e = launch_gather(g, nb, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int fkv_version(void) { return 100; }
+
+const char *fkv_strerror(int status) {
+  switch (status) {
+    case FKV_OK: return "ok";
+    case FKV_EINVAL: return "invalid argument (size, count or flag out of range)";
+    case FKV_ENULL: return "required pointer is NULL";
+    case FKV_EALIGN: return "device pointer or row size not a multiple of 16 bytes";
+    case FKV_EUNSUPPORTED: return "shape not supported by the gfx950 kernels";
+    case FKV_EWORKSPACE: return "problem exceeds the context's workspace";
+    case FKV_EHIP: return "HIP runtime error (see fkv_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+int fkv_last_hip_error(void) { return g_last_hip_error; }
+
+int fkv_check_shape(const fkv_shape *shape) {
+  Resolved r;
+  return resolve(shape, &r);
+}
+
+int fkv_check_counts(const fkv_shape *shape, const int32_t *count_per_seq) {
+  Resolved r;
+  const int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  int off[FKV_MAX_SEQS + 1];
+  return check_counts(r, count_per_seq, off);
+}
+
+size_t fkv_workspace_bytes(int64_t max_total_tokens, int32_t max_seqs) {
+  if (max_total_tokens < 1 || max_seqs < 1 || max_seqs > FKV_MAX_SEQS) return 0;
+  return ws_layout(max_total_tokens, max_seqs).total;
+}
+
+int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_seqs) {
+  if (!out) return FKV_ENULL;
+  *out = nullptr;
+  if (max_total_tokens < 1 || max_total_tokens > INT32_MAX || max_seqs < 1) return FKV_EINVAL;
+  if (max_seqs > FKV_MAX_SEQS) return FKV_EUNSUPPORTED;
+  hipError_t e = hipSetDevice(device);
+  if (e != hipSuccess) return hip_fail(e);
+  fkv_ctx *c = new (std::nothrow) fkv_ctx();
+  if (!c) return FKV_EINVAL;
+  c->device = device;
+  c->max_tokens = max_total_tokens;
+  c->max_seqs = max_seqs;
+  c->lay = ws_layout(max_total_tokens, max_seqs);
+  c->ws = nullptr;
+  c->prof_on = false;
+  c->ev_used = 0;
+  memset(c->ms_acc, 0, sizeof c->ms_acc);
+  memset(c->n_acc, 0, sizeof c->n_acc);
+  e = hipMalloc(reinterpret_cast<void **>(&c->ws), c->lay.total);
+  if (e != hipSuccess) {
+    delete c;
+    return hip_fail(e);
+  }
+  *out = c;
+  return FKV_OK;
+}
+
+int fkv_destroy(fkv_ctx *ctx) {
+  if (!ctx) return FKV_ENULL;
+  for (auto &p : ctx->ev_pool) {
+    (void)hipEventDestroy(p.a);
+    (void)hipEventDestroy(p.b);
+  }
+  const hipError_t e = hipFree(ctx->ws);
+  delete ctx;
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+
+int fkv_score_window(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k,
+                     float *scores_group, float *scores_tsp, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!q_win || !k || (!scores_group && r.sum_p > 0)) return FKV_ENULL;
+  if (misaligned(q_win) || misaligned(k) || misaligned(scores_group) || misaligned(scores_tsp)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  return enqueue_score(ctx, shape, r, q_win, k, scores_group, scores_tsp, static_cast<hipStream_t>(stream));
+}
+
+int fkv_select_topk(fkv_ctx *ctx, const fkv_shape *shape, const float *scores, int32_t n_rows,
+                    const int32_t *k_per_seq, int32_t *idx_out, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if ((!scores && r.sum_p > 0) || !idx_out) return FKV_ENULL;
+  int off[FKV_MAX_SEQS + 1];
+  rc = check_counts(r, k_per_seq, off);
+  if (rc != FKV_OK) return rc;
+  if (n_rows < 1 || n_rows > 65535) return FKV_EINVAL;
+  if (misaligned(scores) || misaligned(idx_out)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  SelectArgs a{};
+  a.n_sets = 1;
+  a.W = r.W;
+  a.n_seq = r.n_seq;
+  for (int b = 0; b <= r.n_seq; ++b) a.cu[b] = r.cu[b];
+  fill_rowset(&a.set[0], scores, r.sum_p, n_rows, idx_out, off, r.n_seq);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timed t(ctx, st, KID_SELECT);
+  const hipError_t e = launch_select(a, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+
+int fkv_gather_rows(fkv_ctx *ctx, const fkv_shape *shape, const void *x, size_t row_bytes,
+                    const int32_t *idx, const int32_t *k_per_seq, void *out, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!x || !idx || !out) return FKV_ENULL;
+  int off[FKV_MAX_SEQS + 1];
+  rc = check_counts(r, k_per_seq, off);
+  if (rc != FKV_OK) return rc;
+  if (row_bytes == 0 || row_bytes > (1u << 30)) return FKV_EINVAL;
+  if (row_bytes % 16 != 0 || misaligned(x) || misaligned(out) || misaligned(idx)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  GatherArgs g{};
+  g.n_jobs = 1;
+  fill_job(&g.job[0], x, out, idx, (int64_t)row_bytes, (int)row_bytes, 1, off, r.n_seq);
+  return enqueue_gather(ctx, g, r, static_cast<hipStream_t>(stream));
+}
+
+int fkv_gather_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const void *v,
+                  const int32_t *idx_kv, const int32_t *budget_per_seq, void *k_out, void *v_out,
+                  void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!k || !idx_kv || !k_out) return FKV_ENULL;
+  if ((v == nullptr) != (v_out == nullptr)) return FKV_ENULL;
+  int off[FKV_MAX_SEQS + 1];
+  rc = check_counts(r, budget_per_seq, off);
+  if (rc != FKV_OK) return rc;
+  if (misaligned(k) || misaligned(v) || misaligned(k_out) || misaligned(v_out) || misaligned(idx_kv)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  const int row_bytes = kHeadDim * 2;
+  GatherArgs g{};
+  g.n_jobs = 0;
+  fill_job(&g.job[g.n_jobs++], k, k_out, idx_kv, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hkv, off, r.n_seq);
+  if (v) fill_job(&g.job[g.n_jobs++], v, v_out, idx_kv, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hkv, off, r.n_seq);
+  return enqueue_gather(ctx, g, r, static_cast<hipStream_t>(stream));
+}
+
+int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k,
+                    const void *v, const int32_t *budget_per_seq, void *k_out, void *v_out,
+                    int32_t *idx_kv, const void *x, size_t x_row_bytes,
+                    const int32_t *k_tsp_per_seq, void *x_out, int32_t *idx_tsp, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!q_win || !k || !v || !k_out || !v_out || !idx_kv) return FKV_ENULL;
+  const bool tsp = x != nullptr;
+  if (tsp != (k_tsp_per_seq != nullptr) || tsp != (x_out != nullptr) || tsp != (idx_tsp != nullptr)) return FKV_ENULL;
+  int off_kv[FKV_MAX_SEQS + 1], off_tsp[FKV_MAX_SEQS + 1];
+  rc = check_counts(r, budget_per_seq, off_kv);
+  if (rc != FKV_OK) return rc;
+  if (tsp) {
+    rc = check_counts(r, k_tsp_per_seq, off_tsp);
+    if (rc != FKV_OK) return rc;
+    if (x_row_bytes == 0 || x_row_bytes > (1u << 30)) return FKV_EINVAL;
+    if (x_row_bytes % 16 != 0) return FKV_EALIGN;
+  }
+  if (misaligned(q_win) || misaligned(k) || misaligned(v) || misaligned(k_out) || misaligned(v_out) ||
+      misaligned(idx_kv) || misaligned(x) || misaligned(x_out) || misaligned(idx_tsp))
+    return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float *sg = reinterpret_cast<float *>(ctx->ws + ctx->lay.scores_group);
+  float *stp = tsp ? reinterpret_cast<float *>(ctx->ws + ctx->lay.scores_tsp) : nullptr;
+  rc = enqueue_score(ctx, shape, r, q_win, k, sg, stp, st);
+  if (rc != FKV_OK) return rc;
+
+  SelectArgs a{};
+  a.W = r.W;
+  a.n_seq = r.n_seq;
+  for (int b = 0; b <= r.n_seq; ++b) a.cu[b] = r.cu[b];
+  a.n_sets = 0;
+  fill_rowset(&a.set[a.n_sets++], sg, r.sum_p, r.Hkv, idx_kv, off_kv, r.n_seq);
+  if (tsp) fill_rowset(&a.set[a.n_sets++], stp, r.sum_p, 1, idx_tsp, off_tsp, r.n_seq);
+  {
+    Timed t(ctx, st, KID_SELECT);
+    const hipError_t e = launch_select(a, st);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+
+  const int row_bytes = kHeadDim * 2;
+  GatherArgs g{};
+  g.n_jobs = 0;
+  if (tsp) fill_job(&g.job[g.n_jobs++], x, x_out, idx_tsp, (int64_t)x_row_bytes, (int)x_row_bytes, 1, off_tsp, r.n_seq);
+  fill_job(&g.job[g.n_jobs++], k, k_out, idx_kv, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hkv, off_kv, r.n_seq);
+  fill_job(&g.job[g.n_jobs++], v, v_out, idx_kv, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hkv, off_kv, r.n_seq);
+  return enqueue_gather(ctx, g, r, st);
+}
+
+int fkv_profile_kernels(void) { return KID_COUNT; }
+
+const char *fkv_profile_kernel_name(int id) { return (id >= 0 && id < KID_COUNT) ? kKernelNames[id] : ""; }
+
+int fkv_profile_enable(fkv_ctx *ctx, int on) {
+  if (!ctx) return FKV_ENULL;
+  if (on && ctx->ev_pool.empty()) {
+    ctx->ev_pool.resize(4096);
+    for (auto &p : ctx->ev_pool) {
+      hipError_t e = hipEventCreate(&p.a);
+      if (e == hipSuccess) e = hipEventCreate(&p.b);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+  }
+  ctx->prof_on = on != 0;
+  return FKV_OK;
+}
+
+int fkv_profile_read(fkv_ctx *ctx, float *ms_out, int32_t *launches_out, int32_t cap) {
+  if (!ctx || !ms_out || !launches_out) return FKV_ENULL;
+  if (cap < KID_COUNT) return FKV_EINVAL;
+  for (size_t i = 0; i < ctx->ev_used; ++i) {
+    EventPair &p = ctx->ev_pool[i];
+    hipError_t e = hipEventSynchronize(p.b);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.a, p.b);
+    if (e != hipSuccess) return hip_fail(e);
+    ctx->ms_acc[p.kid] += ms;
+    ctx->n_acc[p.kid] += 1;
+  }
+  ctx->ev_used = 0;
+  for (int i = 0; i < KID_COUNT; ++i) {
+    ms_out[i] = ctx->ms_acc[i];
+    launches_out[i] = ctx->n_acc[i];
+    ctx->ms_acc[i] = 0.f;
+    ctx->n_acc[i] = 0;
+  }
+  return FKV_OK;
+}
+
+}  // extern "C"

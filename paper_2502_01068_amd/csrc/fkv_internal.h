@@ -1,0 +1,93 @@
+// Internal declarations shared by the HIP translation units of libfastkv_select.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fastkv_select.h"
+
+namespace fkv {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 128-bit load / store
+
+constexpr int kHeadDim = 128;     // d: one KV-head row is 256 bytes = 16 lanes x 16 B
+constexpr int kMaxWindow = 8;     // W <= 8: window index is the low 3 bits of an MFMA row
+constexpr int kMaxGroup = 4;      // G <= 4: head-in-group is the high 2 bits of an MFMA row
+constexpr int kMaxKvHeads = 8;
+constexpr int kRowsPerGroup = 32; // MFMA M: row m = head_in_group * 8 + w
+constexpr int kMaxPoolKernel = 31;
+
+// Kernel ids for the per-kernel timing facility.
+enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_COUNT };
+
+// Sequence map passed by value in the kernel arguments: where each sequence's tokens
+// start and which block range of the launch works on it.
+struct SeqMap {
+  int n_seq;
+  int cu[FKV_MAX_SEQS + 1];   // token offset of sequence b in the packed tensors
+  int blk[FKV_MAX_SEQS + 1];  // first block of sequence b in this launch
+};
+
+// ---- score ------------------------------------------------------------------------------
+struct ScoreArgs {
+  const uint16_t *q_win;  // [B][W][Hq][d]
+  const uint16_t *k;      // [sum L][Hkv][d]
+  float2 *partial;        // [blocks of the stats launch][Hkv*32] (running max, sum) in log2 units
+  float *rowstat;         // [B][Hkv*32]: log2-domain max + log2(sum) per softmax row
+  float *scores_group;    // [Hkv][sum P]
+  float *scores_tsp;      // [sum P] or nullptr
+  SeqMap map;
+  int Hq, Hkv, G, W;
+  float scale_log2e;      // softmax scale * log2(e)
+  int causal;
+  int pool_r;             // pooling radius (kernel = 2r+1)
+  int pool_mode;          // FKV_POOL_AVG / FKV_POOL_MAX
+  int chunk;              // tokens per block in the stats launch
+  int64_t sum_p;          // row stride of scores_group
+};
+
+int stats_chunk_tokens(void);
+int scores_tile_out(int pool_r);
+hipError_t launch_stats(const ScoreArgs &a, int n_blocks, hipStream_t s);
+hipError_t launch_combine(const ScoreArgs &a, hipStream_t s);
+hipError_t launch_scores(const ScoreArgs &a, int n_blocks, hipStream_t s);
+
+// ---- select -----------------------------------------------------------------------------
+struct SelectRowSet {
+  const float *scores;  // rows of length sum P, sequence b at column cu[b] - b*W
+  int64_t row_stride;   // floats between rows
+  int n_rows;
+  int32_t *idx_out;     // [n_rows][cnt_off[n_seq]]
+  int cnt_off[FKV_MAX_SEQS + 1];  // prefix sums of the per-sequence keep counts
+};
+struct SelectArgs {
+  SelectRowSet set[2];
+  int n_sets;
+  int W;
+  int n_seq;
+  int cu[FKV_MAX_SEQS + 1];
+};
+hipError_t launch_select(const SelectArgs &a, hipStream_t s);
+
+// ---- gather -----------------------------------------------------------------------------
+struct GatherJob {
+  const uint8_t *src;
+  uint8_t *dst;
+  const int32_t *idx;     // [n_heads][total_rows]
+  int64_t src_row_stride; // bytes between consecutive tokens in src
+  int row_bytes;          // bytes copied per (head, kept token); multiple of 16
+  int n_heads;            // src offset of head h inside a token row is h*row_bytes
+  int total_rows;         // kept rows per head over all sequences
+  int blk0;               // first block of this job in the launch
+  int cnt_off[FKV_MAX_SEQS + 1];
+};
+struct GatherArgs {
+  GatherJob job[3];
+  int n_jobs;
+  int n_seq;
+  int cu[FKV_MAX_SEQS + 1];
+};
+int gather_blocks(const GatherJob &j);
+hipError_t launch_gather(const GatherArgs &a, int n_blocks, hipStream_t s);
+
+}  // namespace fkv

@@ -1,0 +1,135 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects invalid problems before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_01068_amd import binding as fk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fastkv_select.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(fk.LIB_PATH):
+        from paper_2502_01068_amd import build
+        build.build()
+    return fk.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(fkv_[a-z_]+)\s*\(", text)))
+    assert len(declared) >= 15
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(fk.EXPORTS) == declared
+    assert lib.fkv_version() >= 100
+    assert lib.fkv_profile_kernels() == 5
+    assert lib.fkv_strerror(fk.FKV_EALIGN).decode().startswith("device pointer")
+
+
+def test_shape_struct_matches_header_layout():
+    # int32, pointer (8-aligned), then 8 x 4-byte fields
+    assert ctypes.sizeof(fk.FkvShape) == 4 + 4 + 8 + 4 * 9 + 4
+    assert fk.FkvShape.cu_seqlens.offset == 8 and fk.FkvShape.L.offset == 16
+    assert fk.FkvShape.causal.offset == 16 + 4 * 8
+
+
+def _shape(**kw):
+    lengths = kw.pop("lengths", 2048)
+    return fk.make_shape(lengths, **kw)
+
+
+def test_check_shape_accepts_paper_configs(lib):
+    assert lib.fkv_check_shape(ctypes.byref(_shape())) == fk.FKV_OK
+    assert lib.fkv_check_shape(ctypes.byref(_shape(lengths=[8192, 16384, 9000], pool_mode="avg"))) == fk.FKV_OK
+    assert lib.fkv_check_shape(ctypes.byref(_shape(lengths=8))) == fk.FKV_OK  # L == W: empty prefix
+    assert lib.fkv_check_shape(ctypes.byref(_shape(n_q_heads=8, n_kv_heads=8, window=4, pool_kernel=1))) == fk.FKV_OK
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(lengths=7), fk.FKV_EINVAL),                       # shorter than the window
+    (dict(lengths=[100, 5]), fk.FKV_EINVAL),
+    (dict(pool_kernel=6), fk.FKV_EINVAL),                   # even kernel
+    (dict(pool_kernel=0), fk.FKV_EINVAL),
+    (dict(window=0), fk.FKV_EINVAL),
+    (dict(n_q_heads=30), fk.FKV_EINVAL),                    # not a multiple of Hkv
+    (dict(softmax_scale=-1.0), fk.FKV_EINVAL),
+    (dict(softmax_scale=float("nan")), fk.FKV_EINVAL),
+    (dict(head_dim=64), fk.FKV_EUNSUPPORTED),
+    (dict(window=16), fk.FKV_EUNSUPPORTED),
+    (dict(n_q_heads=64), fk.FKV_EUNSUPPORTED),              # G = 8
+    (dict(n_q_heads=32, n_kv_heads=16), fk.FKV_EUNSUPPORTED),
+    (dict(pool_kernel=33), fk.FKV_EUNSUPPORTED),
+    (dict(lengths=[64] * 65), fk.FKV_EUNSUPPORTED),
+])
+def test_check_shape_rejects(lib, kw, code):
+    assert lib.fkv_check_shape(ctypes.byref(_shape(**kw))) == code
+
+
+def test_check_shape_null_and_flags(lib):
+    assert lib.fkv_check_shape(None) == fk.FKV_ENULL
+    s = _shape(lengths=[100, 200])
+    s.cu_seqlens = None
+    assert lib.fkv_check_shape(ctypes.byref(s)) == fk.FKV_ENULL   # B > 1 needs cu_seqlens
+    s = _shape()
+    s.cu_seqlens = None                                            # B == 1: L is used
+    assert lib.fkv_check_shape(ctypes.byref(s)) == fk.FKV_OK
+    s.L = 3
+    assert lib.fkv_check_shape(ctypes.byref(s)) == fk.FKV_EINVAL
+    s = _shape()
+    s.pool_mode = 2
+    assert lib.fkv_check_shape(ctypes.byref(s)) == fk.FKV_EINVAL
+    s = _shape()
+    s.causal = 5
+    assert lib.fkv_check_shape(ctypes.byref(s)) == fk.FKV_EINVAL
+    bad = fk.make_shape([100, 200])
+    bad._keep[0] = 1                                               # cu[0] != 0
+    assert lib.fkv_check_shape(ctypes.byref(bad)) == fk.FKV_EINVAL
+    bad = fk.make_shape([100, 200])
+    bad._keep[2] = 50                                              # not increasing
+    assert lib.fkv_check_shape(ctypes.byref(bad)) == fk.FKV_EINVAL
+
+
+def test_check_counts(lib):
+    s = _shape(lengths=[100, 200])
+    ok = (ctypes.c_int32 * 2)(8, 200)
+    assert lib.fkv_check_counts(ctypes.byref(s), ok) == fk.FKV_OK
+    assert lib.fkv_check_counts(ctypes.byref(s), (ctypes.c_int32 * 2)(7, 50)) == fk.FKV_EINVAL    # k < W
+    assert lib.fkv_check_counts(ctypes.byref(s), (ctypes.c_int32 * 2)(101, 50)) == fk.FKV_EINVAL  # k > L
+    assert lib.fkv_check_counts(ctypes.byref(s), None) == fk.FKV_ENULL
+
+
+def test_entry_points_validate_before_touching_the_context(lib):
+    # With a NULL context every call must still report the *argument* problem first, and a
+    # valid call must stop at the context check: nothing is launched without a context.
+    s = _shape(lengths=7)
+    assert lib.fkv_score_window(None, ctypes.byref(s), None, None, None, None, None) == fk.FKV_EINVAL
+    s = _shape()
+    assert lib.fkv_score_window(None, ctypes.byref(s), None, None, None, None, None) == fk.FKV_ENULL
+    p16, p8 = ctypes.c_void_p(4096), ctypes.c_void_p(4104)
+    assert lib.fkv_score_window(None, ctypes.byref(s), p8, p16, p16, None, None) == fk.FKV_EALIGN
+    assert lib.fkv_score_window(None, ctypes.byref(s), p16, p16, p16, None, None) == fk.FKV_ENULL  # ctx
+    k = (ctypes.c_int32 * 1)(512)
+    assert lib.fkv_select_topk(None, ctypes.byref(s), p16, 0, k, p16, None) == fk.FKV_EINVAL      # n_rows
+    assert lib.fkv_select_topk(None, ctypes.byref(s), p16, 1, (ctypes.c_int32 * 1)(4), p16, None) == fk.FKV_EINVAL
+    assert lib.fkv_gather_rows(None, ctypes.byref(s), p16, 24, p16, k, p16, None) == fk.FKV_EALIGN  # row bytes
+    assert lib.fkv_gather_rows(None, ctypes.byref(s), p16, 0, p16, k, p16, None) == fk.FKV_EINVAL
+    assert lib.fkv_gather_kv(None, ctypes.byref(s), p16, p16, p16, k, p16, None, None) == fk.FKV_ENULL  # v without v_out
+    assert lib.fkv_compress_kv(None, ctypes.byref(s), p16, p16, p16, k, p16, p16, p16,
+                               p16, 8192, None, p16, p16, None) == fk.FKV_ENULL                   # half a TSP leg
+    assert lib.fkv_compress_kv(None, ctypes.byref(s), p16, p16, p16, k, p16, p16, p16,
+                               None, 0, None, None, None, None) == fk.FKV_ENULL                   # ctx
+    assert lib.fkv_destroy(None) == fk.FKV_ENULL
+
+
+def test_workspace_bytes(lib):
+    small, big = lib.fkv_workspace_bytes(2048, 1), lib.fkv_workspace_bytes(131072, 1)
+    assert 0 < small < big < 64 << 20
+    assert big >= 131072 * 9 * 4
+    assert lib.fkv_workspace_bytes(0, 1) == 0 and lib.fkv_workspace_bytes(100, 65) == 0

@@ -1,0 +1,99 @@
+"""GPU parity at the full benchmark sizes (L = 32K, 128K, the ragged batch), in the launch
+configuration the benchmark times: one fkv_compress_kv call with the TSP leg."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_01068_amd import binding as fk
+from paper_2502_01068_amd import workloads as wl
+from parity import assert_index_set, assert_scores_close, dev_bf16, host_bits
+
+pytestmark = pytest.mark.gpu
+W = 8
+
+
+def _full_check(L, k_tsp, budget, pool_mode, seed):
+    t0 = time.time()
+    s = wl.make_sequence(seed, L)
+    print("  inputs generated in %.1fs" % (time.time() - t0), flush=True)
+    ctx = fk.Context(max_total_tokens=L, max_seqs=1)
+    shape = fk.make_shape(L, pool_mode=pool_mode)
+    q, k, v, x = dev_bf16(s["q_win"]), dev_bf16(s["k"]), dev_bf16(s["v"]), dev_bf16(s["x"])
+    out = ctx.fkv_compress_kv(shape, q, k, v, budget, x=x, k_tsp_per_seq=k_tsp)
+    sg, st = ctx.fkv_score_window(shape, q, k)
+    torch.cuda.synchronize()
+    print("  gpu done", flush=True)
+    t0 = time.time()
+    ref = oracle.score_window(s["q_win"], s["k"], 7, pool_mode, precision="f32")
+    print("  oracle scores in %.1fs on %d threads" % (time.time() - t0, oracle.max_threads()), flush=True)
+    sg, st = sg.cpu().numpy(), st.cpu().numpy()
+    e1 = assert_scores_close(sg, ref["scores_group"], "scores_group")
+    e2 = assert_scores_close(st, ref["scores_tsp"], "scores_tsp")
+    idx_kv, idx_tsp = out["idx_kv"].cpu().numpy(), out["idx_tsp"].cpu().numpy()
+    flips = 0
+    for g in range(8):
+        ref_idx = oracle.select_topk(ref["scores_group"][g], W, budget)
+        flips += assert_index_set(idx_kv[g], ref_idx, ref["scores_group"][g], W, "kv g%d" % g)
+        np.testing.assert_array_equal(idx_kv[g], oracle.select_topk(sg[g], W, budget))
+        np.testing.assert_array_equal(host_bits(out["k_out"][g]), s["k"][idx_kv[g], g])
+        np.testing.assert_array_equal(host_bits(out["v_out"][g]), s["v"][idx_kv[g], g])
+    ref_idx = oracle.select_topk(ref["scores_tsp"], W, k_tsp)
+    flips += assert_index_set(idx_tsp, ref_idx, ref["scores_tsp"], W, "tsp")
+    np.testing.assert_array_equal(idx_tsp, oracle.select_topk(st, W, k_tsp))
+    np.testing.assert_array_equal(host_bits(out["x_out"]), s["x"][idx_tsp])
+    recall = np.isin(s["heavy"], idx_tsp).mean()
+    print("  max rel err group %.2e tsp %.2e; tolerance-band flips %d; heavy recall %.2f" % (e1, e2, flips, recall),
+          flush=True)
+    ctx.close()
+
+
+@pytest.mark.parametrize("pool_mode", ["avg", "max"])
+def test_config2_32k(pool_mode):
+    print("case: config2 L=32768 %s" % pool_mode, flush=True)
+    _full_check(32768, 6554, 2048, pool_mode, seed=0)
+
+
+def test_config3_128k():
+    print("case: config3 L=131072 avg", flush=True)
+    _full_check(131072, 26214, 13107, "avg", seed=0)
+
+
+@pytest.mark.parametrize("budget", [512, 2048])
+def test_config4_ragged(budget):
+    lengths = wl.ragged_lengths(0)
+    print("case: config4 ragged %s budget %d" % (lengths, budget), flush=True)
+    batch = wl.make_batch(0, lengths)
+    ctx = fk.Context(max_total_tokens=sum(lengths), max_seqs=8)
+    shape = fk.make_shape(lengths, pool_mode="avg")
+    q, k, v, x = dev_bf16(batch["q_win"]), dev_bf16(batch["k"]), dev_bf16(batch["v"]), dev_bf16(batch["x"])
+    ktsp = [wl.round_half_up(0.2 * L) for L in lengths]
+    out = ctx.fkv_compress_kv(shape, q, k, v, budget, x=x, k_tsp_per_seq=ktsp)
+    sg, st = ctx.fkv_score_window(shape, q, k)
+    torch.cuda.synchronize()
+    sg, st = sg.cpu().numpy(), st.cpu().numpy()
+    idx_kv, idx_tsp = out["idx_kv"].cpu().numpy(), out["idx_tsp"].cpu().numpy()
+    k_out, x_out = host_bits(out["k_out"]), host_bits(out["x_out"])
+    col = ot = 0
+    flips = 0
+    for b, (s, L) in enumerate(zip(batch["seqs"], lengths)):
+        P = L - W
+        ref = oracle.score_window(s["q_win"], s["k"], 7, "avg", precision="f32")
+        assert_scores_close(sg[:, col:col + P], ref["scores_group"], "scores_group seq %d" % b)
+        assert_scores_close(st[col:col + P], ref["scores_tsp"], "scores_tsp seq %d" % b)
+        for g in range(8):
+            mine = idx_kv[g, b * budget:(b + 1) * budget]
+            flips += assert_index_set(mine, oracle.select_topk(ref["scores_group"][g], W, budget),
+                                      ref["scores_group"][g], W, "kv seq %d g%d" % (b, g))
+            np.testing.assert_array_equal(k_out[g, b * budget:(b + 1) * budget], s["k"][mine, g])
+        mine = idx_tsp[ot:ot + ktsp[b]]
+        flips += assert_index_set(mine, oracle.select_topk(ref["scores_tsp"], W, ktsp[b]), ref["scores_tsp"], W,
+                                  "tsp seq %d" % b)
+        np.testing.assert_array_equal(x_out[ot:ot + ktsp[b]], s["x"][mine])
+        col += P
+        ot += ktsp[b]
+        print("  seq %d ok" % b, flush=True)
+    print("  tolerance-band flips %d" % flips, flush=True)
+    ctx.close()

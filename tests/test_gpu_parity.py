@@ -1,0 +1,301 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle on identical seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_01068_amd import binding as fk
+from paper_2502_01068_amd import workloads as wl
+from parity import assert_index_set, assert_scores_close, dev_bf16, host_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = fk.Context(max_total_tokens=140000, max_seqs=16)
+    yield c
+    c.close()
+
+
+def _oracle_batch(batch_seqs, pool_kernel, pool_mode, causal=True, scale=None, precision="f32"):
+    """Oracle scores of each sequence, concatenated like the library's packed layout."""
+    sg, st = [], []
+    for s in batch_seqs:
+        o = oracle.score_window(s["q_win"], s["k"], pool_kernel, pool_mode, scale=scale, causal=causal,
+                                precision=precision)
+        sg.append(o["scores_group"])
+        st.append(o["scores_tsp"])
+    return np.concatenate(sg, axis=1), np.concatenate(st)
+
+
+# ------------------------------------------------------------------------------------ scores
+
+@pytest.mark.parametrize("pool_mode", ["max", "avg"])
+def test_scores_config1(ctx, pool_mode):
+    print("case: config1 L=2048 pool=%s" % pool_mode, flush=True)
+    s = wl.make_sequence(0, 2048, n_heavy=64, with_v=False, with_x=False)
+    shape = fk.make_shape(2048, pool_mode=pool_mode)
+    sg, st = ctx.fkv_score_window(shape, dev_bf16(s["q_win"]), dev_bf16(s["k"]))
+    for prec in ("f32", "f64"):
+        rg, rt = _oracle_batch([s], 7, pool_mode, precision=prec)
+        e1 = assert_scores_close(sg.cpu().numpy(), rg, "scores_group/" + prec)
+        e2 = assert_scores_close(st.cpu().numpy(), rt, "scores_tsp/" + prec)
+        print("  max rel err vs %s oracle: group %.2e tsp %.2e" % (prec, e1, e2), flush=True)
+
+
+@pytest.mark.parametrize("L,Hq,Hkv,W,pk,causal,scale", [
+    (9, 32, 8, 8, 7, True, 0.0),        # one prefix token
+    (40, 32, 8, 8, 7, True, 0.0),       # less than one MFMA tile
+    (135, 32, 8, 8, 7, True, 0.0),      # ragged tail just past one stats chunk
+    (8 + 122, 32, 8, 8, 7, True, 0.0),  # exactly one score tile
+    (8 + 123, 32, 8, 8, 7, False, 0.0), # one token into the second tile, non-causal
+    (1000, 8, 2, 4, 3, True, 0.0),      # W=4, G=4, Hkv=2
+    (777, 8, 8, 8, 5, True, 0.0),       # G=1
+    (300, 3, 3, 1, 1, True, 0.0),       # W=1, kernel 1: plain softmax row
+    (500, 12, 4, 7, 9, True, 0.05),     # odd W, G=3, custom scale
+    (513, 16, 8, 8, 31, True, 0.0),     # widest supported pooling kernel
+])
+@pytest.mark.parametrize("pool_mode", ["max", "avg"])
+def test_scores_shapes(ctx, L, Hq, Hkv, W, pk, causal, scale, pool_mode):
+    print("case: L=%d Hq=%d Hkv=%d W=%d pk=%d causal=%s scale=%g %s" % (L, Hq, Hkv, W, pk, causal, scale, pool_mode),
+          flush=True)
+    s = wl.make_sequence(3, L, window=W, n_q_heads=Hq, n_kv_heads=Hkv, n_heavy=min(5, L - W), with_v=False,
+                         with_x=False)
+    shape = fk.make_shape(L, n_q_heads=Hq, n_kv_heads=Hkv, window=W, pool_kernel=pk, pool_mode=pool_mode,
+                          causal=causal, softmax_scale=scale)
+    sg, st = ctx.fkv_score_window(shape, dev_bf16(s["q_win"]), dev_bf16(s["k"]))
+    rg, rt = _oracle_batch([s], pk, pool_mode, causal=causal, scale=(scale or None), precision="f64")
+    assert_scores_close(sg.cpu().numpy(), rg, "scores_group")
+    assert_scores_close(st.cpu().numpy(), rt, "scores_tsp")
+
+
+def test_scores_empty_prefix_and_no_tsp(ctx):
+    print("case: L == W and scores_tsp=NULL", flush=True)
+    s = wl.make_sequence(1, 8, n_heavy=0, with_v=False, with_x=False)
+    shape = fk.make_shape(8)
+    sg, st = ctx.fkv_score_window(shape, dev_bf16(s["q_win"]), dev_bf16(s["k"]))
+    torch.cuda.synchronize()
+    assert sg.shape == (8, 0) and st.shape == (0,)
+    s = wl.make_sequence(1, 600, n_heavy=4, with_v=False, with_x=False)
+    shape = fk.make_shape(600)
+    sg, st = ctx.fkv_score_window(shape, dev_bf16(s["q_win"]), dev_bf16(s["k"]), want_tsp=False)
+    assert st is None
+    rg, _ = _oracle_batch([s], 7, "max", precision="f64")
+    assert_scores_close(sg.cpu().numpy(), rg, "scores_group")
+
+
+def test_scores_large_logits_are_stable(ctx):
+    # keys 8x larger: logits of order +-30, far outside what a fixed softmax reference survives
+    print("case: large logits", flush=True)
+    s = wl.make_sequence(9, 700, n_heavy=6, heavy_gain=20.0, with_v=False, with_x=False)
+    shape = fk.make_shape(700, softmax_scale=0.7)
+    sg, st = ctx.fkv_score_window(shape, dev_bf16(s["q_win"]), dev_bf16(s["k"]))
+    rg, rt = _oracle_batch([s], 7, "max", scale=0.7, precision="f64")
+    keep = rg > 1e-30  # fp32 cannot hold what fp64 still resolves below this
+    assert np.isfinite(sg.cpu().numpy()).all()
+    assert_scores_close(np.where(keep, sg.cpu().numpy(), 0), np.where(keep, rg, 0), "scores_group")
+
+
+def test_scores_ragged_batch(ctx):
+    lengths = [300, 1000, 57, 8, 2049, 131]
+    print("case: ragged batch", lengths, flush=True)
+    batch = wl.make_batch(5, lengths, n_heavy=3, with_v=False, with_x=False)
+    for pool_mode in ("max", "avg"):
+        shape = fk.make_shape(lengths, pool_mode=pool_mode)
+        sg, st = ctx.fkv_score_window(shape, dev_bf16(batch["q_win"]), dev_bf16(batch["k"]))
+        rg, rt = _oracle_batch(batch["seqs"], 7, pool_mode, precision="f64")
+        assert_scores_close(sg.cpu().numpy(), rg, "scores_group")
+        assert_scores_close(st.cpu().numpy(), rt, "scores_tsp")
+
+
+# ------------------------------------------------------------------------------------ select
+
+@pytest.mark.parametrize("P,ks", [
+    (0, [8]), (1, [8, 9]), (5, [8, 10, 13]), (64, [8, 9, 40, 72]), (1023, [100, 1031]), (1024, [520]),
+    (1025, [8, 9, 1033]), (5000, [1000, 2500, 5008]), (32760, [2048, 6554]), (131064, [13107, 26214]),
+])
+@pytest.mark.parametrize("ties", [0.0, 0.5])
+def test_select_bit_exact(ctx, P, ks, ties):
+    W, rows = 8, 3
+    print("case: select P=%d ks=%s ties=%g" % (P, ks, ties), flush=True)
+    scores = wl.random_scores(P + 1, rows, P, ties=ties)
+    if P > 10:
+        scores[1, :] = np.float32(0.125)          # a fully tied row
+        scores[2, P // 3: P // 3 + 7] = scores[2].max()  # a max-pool style plateau at the top
+    d = torch.from_numpy(scores).cuda()
+    shape = fk.make_shape(P + W)
+    for k in ks:
+        idx = ctx.fkv_select_topk(shape, d, k).cpu().numpy()
+        for r in range(rows):
+            np.testing.assert_array_equal(idx[r], oracle.select_topk(scores[r], W, k), err_msg="row %d k %d" % (r, k))
+
+
+def test_select_negative_and_zero_scores(ctx):
+    # the API takes any non-NaN fp32: order must hold across sign; -0.0 and +0.0 tie (lower index wins)
+    print("case: select signed scores", flush=True)
+    rng = np.random.default_rng(0)
+    P, W = 3000, 8
+    scores = rng.standard_normal((2, P)).astype(np.float32)
+    scores[0, ::7] = 0.0
+    scores[0, 3::7] = -0.0
+    d = torch.from_numpy(scores).cuda()
+    shape = fk.make_shape(P + W)
+    for k in (8, 500, 1500, 2999, 3008):
+        idx = ctx.fkv_select_topk(shape, d, k).cpu().numpy()
+        for r in range(2):
+            np.testing.assert_array_equal(idx[r], oracle.select_topk(scores[r], W, k))
+
+
+def test_select_ragged(ctx):
+    lengths = [300, 1000, 57, 8, 2049]
+    ks = [100, 8, 57, 8, 1024]
+    print("case: select ragged", lengths, ks, flush=True)
+    W = 8
+    rows = 4
+    sum_p = sum(lengths) - W * len(lengths)
+    scores = wl.random_scores(77, rows, sum_p, ties=0.3)
+    shape = fk.make_shape(lengths)
+    idx = ctx.fkv_select_topk(shape, torch.from_numpy(scores).cuda(), ks).cpu().numpy()
+    assert idx.shape == (rows, sum(ks))
+    col, o = 0, 0
+    for L, k in zip(lengths, ks):
+        P = L - W
+        for r in range(rows):
+            np.testing.assert_array_equal(idx[r, o:o + k], oracle.select_topk(scores[r, col:col + P], W, k))
+        col += P
+        o += k
+
+
+# ------------------------------------------------------------------------------------ gathers
+
+def test_gather_rows_and_kv_bit_exact(ctx):
+    print("case: gathers", flush=True)
+    rng = np.random.default_rng(4)
+    lengths = [700, 64, 1500]
+    ks = [200, 64, 8]
+    shape = fk.make_shape(lengths)
+    total = sum(lengths)
+    for hidden in (4096, 40, 8):  # 8 KiB rows, 80-byte rows, one 16-byte chunk
+        x = rng.integers(0, 65536, size=(total, hidden), dtype=np.uint16)
+        idx = np.concatenate([np.sort(rng.choice(L, k, replace=False)) for L, k in zip(lengths, ks)]).astype(np.int32)
+        out = ctx.fkv_gather_rows(shape, dev_bf16(x), torch.from_numpy(idx).cuda(), ks)
+        ref = np.concatenate([oracle.gather_rows(x[c:c + L], idx[o:o + k])
+                              for c, L, o, k in zip(np.cumsum([0] + lengths[:-1]), lengths,
+                                                    np.cumsum([0] + ks[:-1]), ks)])
+        np.testing.assert_array_equal(host_bits(out), ref)
+    kk = rng.integers(0, 65536, size=(total, 8, 128), dtype=np.uint16)
+    vv = rng.integers(0, 65536, size=(total, 8, 128), dtype=np.uint16)
+    idx_kv = np.stack([np.concatenate([np.sort(rng.choice(L, k, replace=False)) for L, k in zip(lengths, ks)])
+                       for _ in range(8)]).astype(np.int32)
+    ko, vo = ctx.fkv_gather_kv(shape, dev_bf16(kk), dev_bf16(vv), torch.from_numpy(idx_kv).cuda(), ks)
+    cu = np.cumsum([0] + lengths)
+    oo = np.cumsum([0] + ks)
+    for b in range(3):
+        sl = slice(oo[b], oo[b + 1])
+        np.testing.assert_array_equal(host_bits(ko)[:, sl], oracle.gather_kv(kk[cu[b]:cu[b + 1]], idx_kv[:, sl]))
+        np.testing.assert_array_equal(host_bits(vo)[:, sl], oracle.gather_kv(vv[cu[b]:cu[b + 1]], idx_kv[:, sl]))
+    ko2, none = ctx.fkv_gather_kv(shape, dev_bf16(kk), None, torch.from_numpy(idx_kv).cuda(), ks)
+    assert none is None
+    np.testing.assert_array_equal(host_bits(ko2), host_bits(ko))
+
+
+# ------------------------------------------------------------------------------------ fused layer
+
+def _check_layer(ctx, seqs, lengths, budget, k_tsp, pool_mode, what):
+    """compress_kv on the GPU vs the oracle, sequence by sequence."""
+    B = len(lengths)
+    W = 8
+    shape = fk.make_shape(lengths, pool_mode=pool_mode)
+    cat = lambda n: np.concatenate([s[n] for s in seqs], axis=0)
+    q = dev_bf16(np.stack([s["q_win"] for s in seqs]))
+    k, v = dev_bf16(cat("k")), dev_bf16(cat("v"))
+    x = dev_bf16(cat("x")) if k_tsp is not None else None
+    budgets = budget if isinstance(budget, list) else [budget] * B
+    ktsps = (k_tsp if isinstance(k_tsp, list) else [k_tsp] * B) if k_tsp is not None else None
+    out = ctx.fkv_compress_kv(shape, q, k, v, budgets, x=x, k_tsp_per_seq=ktsps)
+    sg, st = ctx.fkv_score_window(shape, q, k)   # the scores the fused call ranked (same kernels)
+    torch.cuda.synchronize()
+    sg, st = sg.cpu().numpy(), st.cpu().numpy()
+    idx_kv = out["idx_kv"].cpu().numpy()
+    k_out, v_out = host_bits(out["k_out"]), host_bits(out["v_out"])
+    n_flip = 0
+    col = ob = ot = 0
+    for b, (s, L) in enumerate(zip(seqs, lengths)):
+        P = L - W
+        ref = oracle.compress_kv(s["q_win"], s["k"], s["v"], budgets[b], 7, pool_mode,
+                                 x=s.get("x") if k_tsp is not None else None,
+                                 k_tsp=ktsps[b] if k_tsp is not None else None)
+        assert_scores_close(sg[:, col:col + P], ref["scores_group"], what + " scores_group seq %d" % b)
+        for g in range(8):
+            mine = idx_kv[g, ob:ob + budgets[b]]
+            n_flip += assert_index_set(mine, ref["idx_kv"][g], ref["scores_group"][g], W, what + " kv g%d" % g)
+            # exact with respect to the scores the GPU itself produced
+            np.testing.assert_array_equal(mine, oracle.select_topk(sg[g, col:col + P], W, budgets[b]))
+            # gathered rows are the rows of the GPU's own indices, bit for bit
+            np.testing.assert_array_equal(k_out[g, ob:ob + budgets[b]], s["k"][mine, g])
+            np.testing.assert_array_equal(v_out[g, ob:ob + budgets[b]], s["v"][mine, g])
+        if k_tsp is not None:
+            assert_scores_close(st[col:col + P], ref["scores_tsp"], what + " scores_tsp seq %d" % b)
+            mine = out["idx_tsp"].cpu().numpy()[ot:ot + ktsps[b]]
+            n_flip += assert_index_set(mine, ref["idx_tsp"], ref["scores_tsp"], W, what + " tsp")
+            np.testing.assert_array_equal(mine, oracle.select_topk(st[col:col + P], W, ktsps[b]))
+            np.testing.assert_array_equal(host_bits(out["x_out"])[ot:ot + ktsps[b]], s["x"][mine])
+            ot += ktsps[b]
+        col += P
+        ob += budgets[b]
+    print("  %s: index flips inside the tolerance band: %d" % (what, n_flip), flush=True)
+    return out
+
+
+@pytest.mark.parametrize("pool_mode", ["avg", "max"])
+def test_compress_kv_config1(ctx, pool_mode):
+    print("case: compress_kv config1 %s" % pool_mode, flush=True)
+    s = wl.make_sequence(0, 2048, n_heavy=64)
+    _check_layer(ctx, [s], [2048], 256, 512, pool_mode, "config1/" + pool_mode)
+
+
+def test_compress_kv_without_tsp_and_edges(ctx):
+    print("case: compress_kv edges", flush=True)
+    s = wl.make_sequence(2, 700, n_heavy=8)
+    _check_layer(ctx, [s], [700], 64, None, "max", "no-tsp")
+    _check_layer(ctx, [s], [700], 8, 8, "max", "window only")        # k == W
+    _check_layer(ctx, [s], [700], 700, 700, "avg", "identity")       # k == L
+    s = wl.make_sequence(2, 8, n_heavy=0)
+    _check_layer(ctx, [s], [8], 8, 8, "max", "L == W")
+
+
+def test_compress_kv_ragged_batch(ctx):
+    lengths = [300, 1000, 57, 2049, 131]
+    print("case: compress_kv ragged", lengths, flush=True)
+    batch = wl.make_batch(8, lengths, n_heavy=3)
+    _check_layer(ctx, batch["seqs"], lengths, [64, 100, 57, 512, 8],
+                 [wl.round_half_up(0.2 * L) for L in lengths], "max", "ragged")
+
+
+def test_deterministic(ctx):
+    print("case: determinism", flush=True)
+    s = wl.make_sequence(4, 3000, n_heavy=30)
+    shape = fk.make_shape(3000)
+    q, k, v, x = dev_bf16(s["q_win"]), dev_bf16(s["k"]), dev_bf16(s["v"]), dev_bf16(s["x"])
+    a = ctx.fkv_compress_kv(shape, q, k, v, 300, x=x, k_tsp_per_seq=600)
+    a = {n: t.clone() for n, t in a.items()}
+    for _ in range(3):
+        b = ctx.fkv_compress_kv(shape, q, k, v, 300, x=x, k_tsp_per_seq=600)
+        for n in a:
+            assert torch.equal(a[n].view(torch.int16) if a[n].dtype == torch.bfloat16 else a[n],
+                               b[n].view(torch.int16) if b[n].dtype == torch.bfloat16 else b[n]), n
+
+
+def test_chain_small(ctx):
+    # Algorithm 1 at reduced size: 6 layers, TSP layer 2; layers after it run on the kept tokens.
+    print("case: chain small", flush=True)
+    L, k_tsp, budget, n_layers, tsp_layer = 1500, wl.round_half_up(0.2 * 1500), 128, 6, 2
+    tokens = 0
+    for layer in range(n_layers):
+        Lc = L if layer <= tsp_layer else k_tsp
+        tokens += Lc
+        s = wl.make_sequence(21, Lc, n_heavy=10, layer=layer)
+        _check_layer(ctx, [s], [Lc], min(budget, Lc), k_tsp if layer == tsp_layer else None, "max",
+                     "chain layer %d" % layer)
+    assert tokens == (tsp_layer + 1) * L + (n_layers - tsp_layer - 1) * k_tsp
