@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the FastKV selection hot path on one MI355X.
+
+One "step" = one fkv_compress_kv call with the TSP leg on the L = 32768 Llama-3-8B-shaped layer
+(score all tokens once, select 2048 tokens per KV head and 6554 TSP tokens, gather K/V and hidden
+rows): the shape of the TSP layer of Algorithm 1.  Inputs are synthetic, seeded and resident in HBM
+before the timed region; steps rotate over several independent input sets so no step finds its
+inputs in the 256 MB last-level cache.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+WORKLOADS = {
+    # name: (L, k_tsp, budget)
+    "config1_L2048": (2048, 512, 256),
+    "config2_L32768": (32768, 6554, 2048),
+    "config3_L131072": (131072, 26214, 13107),
+}
+
+
+def kernel_algorithmic_bytes(L, k_tsp, budget, Hq=32, Hkv=8, d=128, hidden=4096, W=8):
+    """Bytes each kernel must move once (the whole-path figure counts K once, in k_stats)."""
+    P = L - W
+    return {
+        "k_stats": L * Hkv * d * 2 + W * Hq * d * 2,
+        "k_combine": 0,
+        "k_scores": 4 * (Hkv + 1) * P,                       # the scores it writes; its K re-read is overhead
+        "k_select": 4 * (Hkv + 1) * P + 4 * (k_tsp + Hkv * budget),
+        "k_gather": 2 * k_tsp * hidden * 2 + 2 * 2 * Hkv * budget * d * 2 + 4 * (k_tsp + Hkv * budget),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="config2_L32768", choices=sorted(WORKLOADS))
+    ap.add_argument("--pool", default="avg", choices=["avg", "max"])
+    ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated over the steps")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2502_01068_amd import binding as fk
+    from paper_2502_01068_amd import workloads as wl
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import dev_bf16, host_bits
+
+    L, k_tsp, budget = WORKLOADS[args.workload]
+    W = 8
+    torch.cuda.set_device(0)
+    ctx = fk.Context(max_total_tokens=L, max_seqs=1, device=0)
+    shape = fk.make_shape(L, pool_mode=args.pool)
+
+    t_gen = time.time()
+    host0 = wl.make_sequence(args.seed, L)
+    sets = []
+    for i in range(max(1, args.sets)):
+        h = host0 if i == 0 else wl.make_sequence(args.seed + 1000 + i, L)
+        sets.append({n: dev_bf16(h[n]) for n in ("q_win", "k", "v", "x")})
+        if i:
+            del h
+    outs = [None] * len(sets)
+    t_gen = time.time() - t_gen
+
+    def step(i):
+        s = sets[i % len(sets)]
+        outs[i % len(sets)] = ctx.fkv_compress_kv(shape, s["q_win"], s["k"], s["v"], budget, x=s["x"],
+                                                  k_tsp_per_seq=k_tsp, out=outs[i % len(sets)])
+
+    def timed(n_steps, first):
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for i in range(n_steps):
+            step(first + i)
+        ev1.record()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n_steps, ev0.elapsed_time(ev1) / n_steps
+
+    for i in range(args.warmup):
+        step(i)
+    wall_ms, dev_ms = timed(args.steps, 0)               # headline: rotating (cold) inputs
+
+    # warm variant: the same buffers every step
+    saved = sets
+    sets = saved[:1]
+    for i in range(5):
+        step(0)
+    warm_wall_ms, warm_dev_ms = timed(args.steps, 0)
+    sets = saved
+
+    # per-kernel device time (HIP events around every launch, on the launch stream)
+    ctx.fkv_profile_enable(True)
+    n_prof = min(args.steps, 100)
+    for i in range(n_prof):
+        step(i)
+    prof = ctx.fkv_profile_read()
+    ctx.fkv_profile_enable(False)
+    per_kernel_us = {name: 1e3 * ms / max(cnt, 1) for name, (ms, cnt) in prof.items()}
+    alg = kernel_algorithmic_bytes(L, k_tsp, budget)
+    dominant = max(per_kernel_us, key=per_kernel_us.get)
+    dom_gbs = alg[dominant] / (per_kernel_us[dominant] * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dominant)
+        except Exception:
+            traffic = None
+
+    # device-to-device copy bandwidth of this machine, as an achievable ceiling (read + write bytes)
+    big = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(big)
+    for _ in range(3):
+        dst.copy_(big)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        dst.copy_(big)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * big.numel() * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del big, dst
+
+    total_bytes = wl.algorithmic_bytes(L, k_tsp, budget)
+    tokens_per_s = L / (wall_ms * 1e-3)
+    result = {
+        "metric": "context tokens scored+selected+gathered/sec at L=32K; achieved HBM GB/s vs peak",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 inputs, fp32 accumulate and scores, int32 indices",
+        "data": "synthetic (seeded N(0,1) bf16 + 1% planted heavy keys)",
+        "config": {"workload": "%s: 1 layer, batch 1, L=%d, 32 q / 8 kv heads, d=128, hidden 4096, W=8, pool %s 7, "
+                               "k_tsp=%d, kv budget=%d, %d rotating input sets" % (args.workload, L, args.pool, k_tsp,
+                                                                                  budget, len(sets))},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": dom_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_us": per_kernel_us[dominant]},
+        "path": {"algorithmic_bytes": total_bytes, "achieved_GBps": total_bytes / (wall_ms * 1e-3) / 1e9,
+                 "frac_of_peak": total_bytes / (wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "device_ms_per_step": dev_ms, "warm_ms_per_step": warm_wall_ms, "warm_device_ms": warm_dev_ms,
+                 "per_kernel_us": per_kernel_us, "measured_copy_GBps": copy_gbs,
+                 "frac_of_measured_copy": total_bytes / (wall_ms * 1e-3) / 1e9 / copy_gbs},
+        "context": {"paper": "FastKV reports up to 1.82x prefill and 2.87x decode speedup on one NVIDIA A100 SXM "
+                             "(LLaMA-3.1-8B-Instruct); its token-importance estimation costs 0.04 s per 32K prefill "
+                             "(all 32 layers) on that GPU - context, not a target"},
+    }
+
+    # parity spot check in the timed launch configuration (set 0 is the seeded host copy)
+    if not args.no_parity or not args.no_cpu_baseline:
+        import oracle
+        o = outs[0]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ref = oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, 7, args.pool, x=host0["x"],
+                                 k_tsp=k_tsp)
+        t_oracle = time.perf_counter() - t0
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = {"value": L / t_oracle, "unit": "tokens/s", "cores": oracle.max_threads(),
+                                      "kind": "oracle",
+                                      "sample": "the whole %s layer once (score, 9 selects, gathers): %.2f s" % (
+                                          args.workload, t_oracle)}
+        if not args.no_parity:
+            from parity import assert_index_set
+            flips = 0
+            idx_kv, idx_tsp = o["idx_kv"].cpu().numpy(), o["idx_tsp"].cpu().numpy()
+            for g in range(8):
+                flips += assert_index_set(idx_kv[g], ref["idx_kv"][g], ref["scores_group"][g], W, "bench kv g%d" % g)
+                np.testing.assert_array_equal(host_bits(o["k_out"][g]), host0["k"][idx_kv[g], g])
+            flips += assert_index_set(idx_tsp, ref["idx_tsp"], ref["scores_tsp"], W, "bench tsp")
+            np.testing.assert_array_equal(host_bits(o["x_out"]), host0["x"][idx_tsp])
+            result["parity"] = {"index_sets": "match (tolerance-band flips: %d)" % flips, "gathers": "bit-exact"}
+    result["setup_s"] = {"input_generation": t_gen}
+    print(json.dumps(result))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()
