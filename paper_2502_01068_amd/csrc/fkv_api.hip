@@ -153,6 +153,7 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
   a.q_win = static_cast<const uint16_t *>(q_win);
   a.k = static_cast<const uint16_t *>(k);
   a.partial = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.partial);
+  a.partial_stride = ctx->lay.max_stat_blocks;
   a.rowstat = reinterpret_cast<float *>(ctx->ws + ctx->lay.rowstat);
   a.scores_group = scores_group;
   a.scores_tsp = scores_tsp;
@@ -223,8 +224,15 @@ int enqueue_gather(fkv_ctx *ctx, GatherArgs &g, const Resolved &r, hipStream_t s
   for (int b = 0; b <= r.n_seq; ++b) g.cu[b] = r.cu[b];
   int nb = 0;
   for (int i = 0; i < g.n_jobs; ++i) {
-    g.job[i].blk0 = nb;
-    nb += gather_blocks(g.job[i]);
+    GatherJob &j = g.job[i];
+    if ((int64_t)j.total_rows * (j.row_bytes / 16) >= (int64_t)1 << 31) return FKV_EUNSUPPORTED;
+    const int cpr = j.row_bytes / 16;
+    j.cpr_shift = -1;
+    for (int sft = 0; sft < 31; ++sft)
+      if ((1 << sft) == cpr) j.cpr_shift = sft;
+    j.blk0 = nb;
+    j.blocks_per_head = gather_blocks_per_head(j);
+    nb += j.blocks_per_head * j.n_heads;
   }
   if (nb == 0) return FKV_OK;
   Timed t(ctx, st, KID_GATHER);

@@ -4,15 +4,19 @@
 //
 // The unit of work is one 16-byte chunk; consecutive lanes take consecutive chunks of a row,
 // so a 256-byte K/V head row is one 16-lane segment and an 8 KiB hidden row is 512 lanes.
+// Each (job, head) owns a contiguous range of blocks, so the head and job lookups are scalar.
 #include "fkv_internal.h"
 
 namespace fkv {
 
 constexpr int kGatherThreads = 256;
-constexpr int kGatherUnroll = 4;  // 16-byte chunks in flight per thread
+#ifndef FKV_GATHER_UNROLL
+#define FKV_GATHER_UNROLL 4
+#endif
+constexpr int kGatherUnroll = FKV_GATHER_UNROLL;  // 16-byte chunks in flight per thread
 
-int gather_blocks(const GatherJob &j) {
-  const int64_t chunks = (int64_t)j.n_heads * j.total_rows * (j.row_bytes / 16);
+int gather_blocks_per_head(const GatherJob &j) {
+  const int64_t chunks = (int64_t)j.total_rows * (j.row_bytes / 16);
   const int64_t per_block = (int64_t)kGatherThreads * kGatherUnroll;
   return (int)((chunks + per_block - 1) / per_block);
 }
@@ -21,32 +25,35 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(GatherArgs a) {
   int ji = 0;
   while (ji + 1 < a.n_jobs && (int)blockIdx.x >= a.job[ji + 1].blk0) ++ji;
   const GatherJob &job = a.job[ji];
-  const int cpr = job.row_bytes >> 4;  // chunks per row
-  const int64_t n_chunks = (int64_t)job.n_heads * job.total_rows * cpr;
-  const int64_t c0 = ((int64_t)((int)blockIdx.x - job.blk0) * kGatherUnroll) * kGatherThreads + threadIdx.x;
+  const uint32_t rel = blockIdx.x - job.blk0;
+  const uint32_t h = rel / (uint32_t)job.blocks_per_head;  // uniform: scalar division
+  const uint32_t hb = rel - h * job.blocks_per_head;
+  const uint32_t cpr = (uint32_t)job.row_bytes >> 4;       // chunks per row
+  const uint32_t n_chunks = (uint32_t)job.total_rows * cpr; // per head; host guarantees < 2^31
+  const uint32_t c0 = hb * (kGatherUnroll * kGatherThreads) + threadIdx.x;
+  const int32_t *idx = job.idx + (size_t)h * job.total_rows;
+  const uint8_t *src_h = job.src + (size_t)h * job.row_bytes;
+  u32x4 *dst_h = reinterpret_cast<u32x4 *>(job.dst + (size_t)h * job.total_rows * job.row_bytes);
 
   u32x4 val[kGatherUnroll];
-  int64_t dst_off[kGatherUnroll];
+  bool live[kGatherUnroll];
 #pragma unroll
   for (int u = 0; u < kGatherUnroll; ++u) {
-    const int64_t c = c0 + (int64_t)u * kGatherThreads;
-    dst_off[u] = -1;
-    if (c < n_chunks) {
-      const int64_t rowi = c / cpr;            // h * total_rows + t
-      const int col = (int)(c - rowi * cpr);
-      const int h = (int)(rowi / job.total_rows);
-      const int t = (int)(rowi - (int64_t)h * job.total_rows);
+    const uint32_t c = c0 + u * kGatherThreads;
+    live[u] = c < n_chunks;
+    if (live[u]) {
+      uint32_t t, col;
+      if (job.cpr_shift >= 0) { t = c >> job.cpr_shift; col = c & (cpr - 1u); }
+      else { t = c / cpr; col = c - t * cpr; }
       int b = 0;
-      while (b + 1 < a.n_seq && t >= job.cnt_off[b + 1]) ++b;
-      const int tok = a.cu[b] + job.idx[rowi];
-      const uint8_t *src = job.src + (size_t)tok * job.src_row_stride + (size_t)h * job.row_bytes;
-      val[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src) + col);
-      dst_off[u] = c;
+      while (b + 1 < a.n_seq && (int)t >= job.cnt_off[b + 1]) ++b;
+      const size_t tok = (size_t)a.cu[b] + (size_t)idx[t];
+      val[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src_h + tok * job.src_row_stride) + col);
     }
   }
 #pragma unroll
   for (int u = 0; u < kGatherUnroll; ++u)
-    if (dst_off[u] >= 0) __builtin_nontemporal_store(val[u], reinterpret_cast<u32x4 *>(job.dst) + dst_off[u]);
+    if (live[u]) __builtin_nontemporal_store(val[u], dst_h + (c0 + u * kGatherThreads));
 }
 
 hipError_t launch_gather(const GatherArgs &a, int n_blocks, hipStream_t s) {

@@ -32,7 +32,8 @@ struct SeqMap {
 struct ScoreArgs {
   const uint16_t *q_win;  // [B][W][Hq][d]
   const uint16_t *k;      // [sum L][Hkv][d]
-  float2 *partial;        // [blocks of the stats launch][Hkv*32] (running max, sum) in log2 units
+  float2 *partial;        // [Hkv*32][partial_stride]: per stats block (running max, sum), log2 units
+  int partial_stride;     // blocks the workspace was sized for
   float *rowstat;         // [B][Hkv*32]: log2-domain max + log2(sum) per softmax row
   float *scores_group;    // [Hkv][sum P]
   float *scores_tsp;      // [sum P] or nullptr
@@ -79,6 +80,8 @@ struct GatherJob {
   int n_heads;            // src offset of head h inside a token row is h*row_bytes
   int total_rows;         // kept rows per head over all sequences
   int blk0;               // first block of this job in the launch
+  int blocks_per_head;    // blocks that cover one head's kept rows
+  int cpr_shift;          // log2(row_bytes/16) when that is a power of two, else -1
   int cnt_off[FKV_MAX_SEQS + 1];
 };
 struct GatherArgs {
@@ -87,7 +90,7 @@ struct GatherArgs {
   int n_seq;
   int cu[FKV_MAX_SEQS + 1];
 };
-int gather_blocks(const GatherJob &j);
+int gather_blocks_per_head(const GatherJob &j);
 hipError_t launch_gather(const GatherArgs &a, int n_blocks, hipStream_t s);
 
 }  // namespace fkv
