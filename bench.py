@@ -36,6 +36,7 @@ def kernel_algorithmic_bytes(L, k_tsp, budget, Hq=32, Hkv=8, d=128, hidden=4096,
         "k_scores": 4 * (Hkv + 1) * P,                       # the scores it writes; its K re-read is overhead
         "k_select": 4 * (Hkv + 1) * P + 4 * (k_tsp + Hkv * budget),
         "k_gather": 2 * k_tsp * hidden * 2 + 2 * 2 * Hkv * budget * d * 2 + 4 * (k_tsp + Hkv * budget),
+        "k_score_fused": L * Hkv * d * 2 + W * Hq * d * 2 + 4 * (Hkv + 1) * P,   # K once + the scores it writes
     }
 
 

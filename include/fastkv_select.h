@@ -137,6 +137,18 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
                     int32_t *idx_kv, const void *x, size_t x_row_bytes,
                     const int32_t *k_tsp_per_seq, void *x_out, int32_t *idx_tsp, void *stream);
 
+/* Which kernels compute the scores.  0 (default): the single-pass kernel (K read once; all its
+ * blocks must be resident at once, about 37K tokens per call on 256 CUs) when the batch fits,
+ * else the two-pass kernels; 1: always two-pass; 2: single-pass or FKV_EUNSUPPORTED.  Both give
+ * the same scores up to fp32 summation order. */
+int fkv_set_score_path(fkv_ctx *ctx, int mode);
+
+/* Synchronises the device and reports the context's sticky error flag: 0, or 1 if a block of the
+ * single-pass score kernel gave up waiting for the rest of its grid (2 s bound; scores of that
+ * call are then unwritten).  Cannot happen while the library's launches are the only work
+ * competing for the device's compute units for that long. */
+int fkv_query_error(fkv_ctx *ctx, int32_t *flag_out);
+
 /* Per-kernel device timing for benchmarks.  While enabled, every launch is bracketed by
  * HIP events on the caller's stream.  fkv_profile_read synchronises those events, writes
  * the accumulated milliseconds and launch counts of kernel ids 0 .. n-1 (n =

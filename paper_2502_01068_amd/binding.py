@@ -21,7 +21,7 @@ EXPORTS = [
     "fkv_version", "fkv_strerror", "fkv_last_hip_error", "fkv_check_shape", "fkv_check_counts",
     "fkv_workspace_bytes", "fkv_create", "fkv_destroy", "fkv_score_window", "fkv_select_topk",
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
-    "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read",
+    "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
 ]
 
 
@@ -70,6 +70,8 @@ def load():
     lib.fkv_gather_rows.argtypes = [vp, shp, vp, sz, vp, pi32, vp, vp]
     lib.fkv_gather_kv.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
     lib.fkv_compress_kv.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp, vp, sz, pi32, vp, vp, vp]
+    lib.fkv_set_score_path.argtypes = [vp, ctypes.c_int]
+    lib.fkv_query_error.argtypes = [vp, pi32]
     lib.fkv_profile_kernels.restype = ctypes.c_int
     lib.fkv_profile_kernel_name.restype = ctypes.c_char_p
     lib.fkv_profile_kernel_name.argtypes = [ctypes.c_int]
@@ -242,6 +244,15 @@ class Context:
             t_arr if tsp else None, _dev_ptr(out.get("x_out"), "x_out", None, True),
             _dev_ptr(out.get("idx_tsp"), "idx_tsp", (torch.int32,), True), _stream()), "fkv_compress_kv")
         return out
+
+    def fkv_set_score_path(self, mode):
+        """0 auto, 1 two-pass kernels, 2 single-pass resident-grid kernel."""
+        _check(load().fkv_set_score_path(self.handle, int(mode)), "fkv_set_score_path")
+
+    def fkv_query_error(self):
+        flag = ctypes.c_int32(0)
+        _check(load().fkv_query_error(self.handle, ctypes.byref(flag)), "fkv_query_error")
+        return int(flag.value)
 
     # ---- timing facility -----------------------------------------------------------------
     def fkv_profile_enable(self, on=True):

@@ -18,7 +18,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-  size_t partial, rowstat, scores_group, scores_tsp, total;
+  size_t partial, rowstat, scores_group, scores_tsp, counters, bpartial, cpartial, total;
   int max_stat_blocks;
 };
 
@@ -31,6 +31,9 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
   w.rowstat = off;      off += align_up((size_t)max_seqs * kMaxKvHeads * kRowsPerGroup * sizeof(float));
   w.scores_group = off; off += align_up((size_t)max_tokens * kMaxKvHeads * sizeof(float));
   w.scores_tsp = off;   off += align_up((size_t)max_tokens * sizeof(float));
+  w.counters = off;     off += align_up((size_t)kNumCounters * sizeof(unsigned));
+  w.bpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxFusedBlocks * sizeof(float2));
+  w.cpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxClusters * sizeof(float2));
   w.total = off;
   return w;
 }
@@ -45,6 +48,8 @@ struct fkv_ctx {
   int32_t max_seqs;
   WsLayout lay;
   uint8_t *ws;
+  int n_cu;            // compute units x resident blocks per CU of the single-pass score kernel
+  int score_path;      // 0 auto, 1 two-pass kernels, 2 single-pass resident grid
   bool prof_on;
   std::vector<EventPair> ev_pool;
   size_t ev_used;
@@ -54,7 +59,7 @@ struct fkv_ctx {
 
 namespace {
 
-const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather"};
+const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather", "k_score_fused"};
 
 int hip_fail(hipError_t e) {
   g_last_hip_error = (int)e;
@@ -167,6 +172,41 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
   a.sum_p = r.sum_p;
   fill_map(r, &a.map);
 
+  // Single pass over K when every block of the batch can be resident at once.
+  {
+    FusedArgs f{};
+    const int cap_own = fused_slots() - a.pool_r - (a.pool_r > r.W ? a.pool_r : r.W);
+    int total = 0, clusters = 0;
+    bool fits = cap_own >= 1 && ctx->score_path != 1;
+    f.cl0[0] = 0;
+    for (int b = 0; b < r.n_seq && fits; ++b) {
+      const int P = r.cu[b + 1] - r.cu[b] - r.W;
+      const int nb_b = (P + cap_own - 1) / cap_own;
+      a.map.blk[b] = total;
+      f.own[b] = nb_b ? (P + nb_b - 1) / nb_b : 0;
+      total += nb_b;
+      clusters += (nb_b + fused_cluster_size() - 1) / fused_cluster_size();
+      f.cl0[b + 1] = clusters;
+      if (total > ctx->n_cu || total > kMaxFusedBlocks || clusters > kMaxClusters) fits = false;
+    }
+    if (ctx->score_path == 2 && !(fits && total > 0)) return FKV_EUNSUPPORTED;
+    if (fits && total > 0) {
+      a.map.blk[r.n_seq] = total;
+      f.counters = reinterpret_cast<unsigned *>(ctx->ws + ctx->lay.counters);
+      f.bpartial = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.bpartial);
+      f.bpartial_stride = kMaxFusedBlocks;
+      f.cpartial = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.cpartial);
+      f.cpartial_stride = kMaxClusters;
+      f.n_wg = total;
+      f.n_clusters = clusters;
+      f.timeout_ticks = 200000000ull;  // 2 s
+      Timed t(ctx, st, KID_SCORE_FUSED);
+      const hipError_t e = launch_score_fused(a, f, st);
+      return e == hipSuccess ? FKV_OK : hip_fail(e);
+    }
+    if (r.sum_p == 0) return FKV_OK;  // no prefix token anywhere: nothing to score
+  }
+
   // pass 1: softmax statistics of every window row over all L keys
   int nb = 0;
   for (int b = 0; b < r.n_seq; ++b) {
@@ -242,6 +282,13 @@ int enqueue_gather(fkv_ctx *ctx, GatherArgs &g, const Resolved &r, hipStream_t s
 
 }  // namespace
 
+#ifdef FKV_TIMING
+namespace fkv { __device__ unsigned long long fkv_ticks[64]; }
+extern "C" int fkv_debug_read_ticks(unsigned long long *out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(fkv::fkv_ticks), sizeof(unsigned long long) * 64);
+}
+#endif
+
 extern "C" {
 
 int fkv_version(void) { return 100; }
@@ -293,12 +340,22 @@ int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_
   c->max_seqs = max_seqs;
   c->lay = ws_layout(max_total_tokens, max_seqs);
   c->ws = nullptr;
+  c->score_path = 0;
+  {
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, device);
+    if (e != hipSuccess) { delete c; return hip_fail(e); }
+    const int per_cu = score_fused_max_blocks_per_cu();
+    c->n_cu = prop.multiProcessorCount * (per_cu > 0 ? 1 : 0);  // one resident block per CU
+  }
   c->prof_on = false;
   c->ev_used = 0;
   memset(c->ms_acc, 0, sizeof c->ms_acc);
   memset(c->n_acc, 0, sizeof c->n_acc);
   e = hipMalloc(reinterpret_cast<void **>(&c->ws), c->lay.total);
+  if (e == hipSuccess) e = hipMemset(c->ws + c->lay.counters, 0, kNumCounters * sizeof(unsigned));
   if (e != hipSuccess) {
+    if (c->ws) (void)hipFree(c->ws);
     delete c;
     return hip_fail(e);
   }
@@ -446,6 +503,23 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
   fill_job(&g.job[g.n_jobs++], k, k_out, idx_kv, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hkv, off_kv, r.n_seq);
   fill_job(&g.job[g.n_jobs++], v, v_out, idx_kv, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hkv, off_kv, r.n_seq);
   return enqueue_gather(ctx, g, r, st);
+}
+
+int fkv_set_score_path(fkv_ctx *ctx, int mode) {
+  if (!ctx) return FKV_ENULL;
+  if (mode < 0 || mode > 2) return FKV_EINVAL;
+  ctx->score_path = mode;
+  return FKV_OK;
+}
+
+int fkv_query_error(fkv_ctx *ctx, int32_t *flag_out) {
+  if (!ctx || !flag_out) return FKV_ENULL;
+  unsigned v = 0;
+  const hipError_t e = hipMemcpy(&v, ctx->ws + ctx->lay.counters + kCtrError * sizeof(unsigned), sizeof v,
+                                 hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(e);
+  *flag_out = (int32_t)v;
+  return FKV_OK;
 }
 
 int fkv_profile_kernels(void) { return KID_COUNT; }

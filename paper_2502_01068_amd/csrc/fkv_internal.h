@@ -17,8 +17,23 @@ constexpr int kMaxKvHeads = 8;
 constexpr int kRowsPerGroup = 32; // MFMA M: row m = head_in_group * 8 + w
 constexpr int kMaxPoolKernel = 31;
 
+// Phase timestamps for kernel tuning builds (-DFKV_TIMING): block (0,0), thread 0 stores the
+// 100 MHz wall clock into fkv_ticks[i].  Compiles to nothing in the product build.
+#ifdef FKV_TIMING
+extern __device__ unsigned long long fkv_ticks[64];
+#define FKV_TICK(i)                                                                         \
+  do {                                                                                      \
+    if (threadIdx.x == 0 && blockIdx.x == FKV_TIMING_BLOCK && blockIdx.y == 0) fkv::fkv_ticks[i] = wall_clock64(); \
+  } while (0)
+#else
+#define FKV_TICK(i) ((void)0)
+#endif
+#ifndef FKV_TIMING_BLOCK
+#define FKV_TIMING_BLOCK 0
+#endif
+
 // Kernel ids for the per-kernel timing facility.
-enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_COUNT };
+enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_SCORE_FUSED, KID_COUNT };
 
 // Sequence map passed by value in the kernel arguments: where each sequence's tokens
 // start and which block range of the launch works on it.
@@ -46,6 +61,29 @@ struct ScoreArgs {
   int chunk;              // tokens per block in the stats launch
   int64_t sum_p;          // row stride of scores_group
 };
+
+// Single-pass (resident grid) score kernel: per-launch plan and grid-exchange buffers.
+constexpr int kMaxFusedBlocks = 512;  // upper bound on resident blocks (CUs) the exchange buffers hold
+constexpr int kMaxClusters = FKV_MAX_SEQS + 32;
+constexpr int kCtrDone = kMaxClusters, kCtrExit = kMaxClusters + 1, kCtrError = kMaxClusters + 2;
+constexpr int kNumCounters = 128;
+static_assert(kCtrError < kNumCounters, "counter block");
+struct FusedArgs {
+  unsigned *counters;      // [kNumCounters], zero between launches
+  float2 *bpartial;        // [Hkv*32][bpartial_stride]: per block (max, sum), log2 units
+  int bpartial_stride;
+  float2 *cpartial;        // [Hkv*32][cpartial_stride]: per cluster (max, sum)
+  int cpartial_stride;
+  int n_wg;                // blocks of the launch (all resident at once)
+  int n_clusters;
+  unsigned long long timeout_ticks;  // bound of the grid wait, 100 MHz ticks
+  int own[FKV_MAX_SEQS];             // prefix tokens owned by each block of sequence b
+  int cl0[FKV_MAX_SEQS + 1];         // first cluster of sequence b
+};
+int fused_slots(void);
+int fused_cluster_size(void);
+int score_fused_max_blocks_per_cu(void);
+hipError_t launch_score_fused(const ScoreArgs &a, const FusedArgs &f, hipStream_t s);
 
 int stats_chunk_tokens(void);
 int scores_tile_out(int pool_r);

@@ -17,98 +17,12 @@
 // 8 KiB LDS tile with an XOR swizzle on the 16-byte column, and reads it back in the MFMA
 // operand layout (lane = token).  The next sub-tile's global loads are issued before the
 // current one is consumed.
-#include "fkv_internal.h"
+#include "fkv_score_common.h"
 
 namespace fkv {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float floatx16;
-
-constexpr int kWaves = 8;            // one wave per KV head
-constexpr int kThreads = kWaves * 64;
-constexpr int kStatsChunk = 128;     // tokens per block in k_stats
-constexpr int kTile = 128;           // tokens computed per block in k_scores (incl. pooling halo)
-constexpr int kSub = 32;             // tokens per MFMA sub-tile
-constexpr int kStageBytes = kSub * kHeadDim * 2;  // 8 KiB per wave
-constexpr float kNegBig = -1.0e30f;
-
 int stats_chunk_tokens(void) { return kStatsChunk; }
 int scores_tile_out(int pool_r) { return kTile - 2 * pool_r; }
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-__device__ __forceinline__ int find_seq(const SeqMap &map, int block) {
-  int b = 0;
-  while (b + 1 < map.n_seq && block >= map.blk[b + 1]) ++b;
-  return b;
-}
-
-// Orders this wave's LDS traffic (writes of one layout, reads of another) without a block barrier.
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// MFMA A operand for KV group g: lane (m = lane%32, hi = lane/32) holds, for step s, the 8
-// values d = hi*64 + s*8 .. +7 of query row m (head g*G + m/8, window row m%8).  The
-// contraction index may be permuted freely as long as K uses the same permutation.
-__device__ __forceinline__ void load_q(const ScoreArgs &a, int b, int g, int lane, bf16x8 (&qa)[8]) {
-  const int m = lane & 31, hi = lane >> 5;
-  const int hl = m >> 3, w = m & 7;
-  const bool ok = hl < a.G && w < a.W;
-  const u32x4 *src = reinterpret_cast<const u32x4 *>(
-      a.q_win + (((size_t)b * a.W + (ok ? w : 0)) * a.Hq + (size_t)g * a.G + (ok ? hl : 0)) * kHeadDim + hi * 64);
-#pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    u32x4 v = src[s];
-    if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
-    qa[s] = __builtin_bit_cast(bf16x8, v);
-  }
-}
-
-// Streams the K rows of one KV head for `n_sub` consecutive 32-token sub-tiles starting at
-// sequence-local token `first` (tokens are clamped into [0, Lb-1] for the load; the caller masks
-// what lies outside its range).  fn(st, acc) receives the raw logits of sub-tile st:
-// acc[r] = q_row(m) . k(token first + st*32 + lane%32) with m = (r/4)*8 + (lane/32)*4 + r%4,
-// i.e. head r/4 of the group and window row (lane/32)*4 + r%4.
-template <typename F>
-__device__ __forceinline__ void stream_head(const ScoreArgs &a, const bf16x8 (&qa)[8], int tok_base, int Lb, int g,
-                                            int first, int n_sub, uint8_t *stage, int lane, F fn) {
-  const int c = lane & 15;        // 16-byte column of the 256-byte head row
-  const int tq = lane >> 4;       // token within a quad of 4 tokens per load instruction
-  const int n = lane & 31, hi = lane >> 5;
-  const uint16_t *kbase = a.k + (size_t)g * kHeadDim + c * 8;
-  const size_t tok_stride = (size_t)a.Hkv * kHeadDim;
-
-  u32x4 nxt[8];
-  auto issue = [&](int st) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int t = first + st * kSub + i * 4 + tq;
-      t = min(max(t, 0), Lb - 1);
-      nxt[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)(tok_base + t) * tok_stride);
-    }
-  };
-  issue(0);
-  for (int st = 0; st < n_sub; ++st) {
-    wave_lds_sync();  // previous sub-tile's reads are done before the tile is overwritten
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int t = i * 4 + tq;  // token slot in the tile
-      *reinterpret_cast<u32x4 *>(stage + t * 256 + ((c ^ (t & 15)) << 4)) = nxt[i];
-    }
-    if (st + 1 < n_sub) issue(st + 1);
-    wave_lds_sync();
-    floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const u32x4 kb = *reinterpret_cast<const u32x4 *>(stage + n * 256 + (((hi * 8 + s) ^ (n & 15)) << 4));
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], __builtin_bit_cast(bf16x8, kb), acc, 0, 0, 0);
-    }
-    fn(st, acc);
-  }
-}
 
 __global__ __launch_bounds__(kThreads) void k_stats(ScoreArgs a) {
   __shared__ __attribute__((aligned(16))) uint8_t stage_all[kWaves * kStageBytes];
@@ -123,6 +37,7 @@ __global__ __launch_bounds__(kThreads) void k_stats(ScoreArgs a) {
   const int n_sub = (t1 - t0 + kSub - 1) / kSub;
   uint8_t *stage = stage_all + wave * kStageBytes;
 
+  FKV_TICK(16);
   for (int g = wave; g < a.Hkv; g += kWaves) {
     bf16x8 qa[8];
     load_q(a, b, g, lane, qa);
@@ -137,24 +52,19 @@ __global__ __launch_bounds__(kThreads) void k_stats(ScoreArgs a) {
       for (int r = 0; r < 16; ++r) {
         const int w = hi * 4 + (r & 3);
         const bool ok = valid && (!a.causal || tok <= P + w);
+        // online softmax with one exponential per element: e = 2^-|z - max|
         const float z = ok ? acc[r] * a.scale_log2e : kNegBig;
-        const float mn = fmaxf(mx[r], z);
-        sm[r] = sm[r] * fast_exp2(mx[r] - mn) + (ok ? fast_exp2(z - mn) : 0.f);
-        mx[r] = mn;
+        const float d = z - mx[r];
+        const float e = fast_exp2(-fabsf(d));
+        sm[r] = d > 0.f ? sm[r] * e + 1.f : sm[r] + (ok ? e : 0.f);
+        mx[r] = fmaxf(mx[r], z);
       }
     });
-    // fold the 32 lanes that share `hi` (fixed butterfly order: deterministic)
-    float2 *dst = a.partial + (size_t)(g * kRowsPerGroup) * a.partial_stride + blockIdx.x;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float M = mx[r];
-#pragma unroll
-      for (int off = 1; off < 32; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
-      float S = sm[r] * fast_exp2(mx[r] - M);
-#pragma unroll
-      for (int off = 1; off < 32; off <<= 1) S += __shfl_xor(S, off);
-      if (n == 0) dst[(size_t)((r >> 2) * 8 + hi * 4 + (r & 3)) * a.partial_stride] = make_float2(M, S);
-    }
+    FKV_TICK(17);
+    const float2 ms = fold_rows(mx, sm, reinterpret_cast<float *>(stage), lane);
+    if (lane < 32)
+      a.partial[(size_t)(g * kRowsPerGroup + lane) * a.partial_stride + blockIdx.x] = ms;
+    FKV_TICK(18);
   }
 }
 
@@ -209,6 +119,7 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
   uint8_t *stage = lds_all + wave * kStageBytes;
   constexpr int kNSub = kTile / kSub;
 
+  FKV_TICK(24);
   // window-summed probabilities of this wave's group: hsum[st][hl] for token j0 + st*32 + n
   float hsum[kNSub][4];
   int g_mine = -1;
@@ -237,7 +148,9 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
       }
     });
   }
+  FKV_TICK(25);
   __syncthreads();
+  FKV_TICK(26);
   if (g_mine >= 0 && hi == 0) {
 #pragma unroll
     for (int st = 0; st < kNSub; ++st) {
@@ -250,39 +163,9 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
   }
   __syncthreads();
 
-  // Pool each head over the token axis (Eq. 1), then mean over the group's heads (App. B.1).
-  // Taps outside [0,P) hold 0: neutral for max (scores are >= 0) and the zero padding of avg.
   const int col0 = tok_base - b * a.W;  // column of this sequence's token 0 in the score rows
-  for (int i = threadIdx.x; i < tout * a.Hkv; i += kThreads) {
-    const int g = i / tout, jj = i - g * tout;
-    const int c = jj + r;
-    float gs = 0.f;
-    for (int hl = 0; hl < a.G; ++hl) {
-      const float *row = s_head[g * kMaxGroup + hl];
-      float p;
-      if (a.pool_mode == FKV_POOL_MAX) {
-        p = row[c];
-        for (int t = -r; t <= r; ++t) p = fmaxf(p, row[c + t]);
-      } else {
-        p = 0.f;
-        for (int t = -r; t <= r; ++t) p += row[c + t];
-        p = p / (float)(2 * r + 1);
-      }
-      gs += p;
-    }
-    g_sum[g][jj] = gs;
-    const int j = j0 + c;
-    if (j < P) a.scores_group[(size_t)g * a.sum_p + col0 + j] = gs / (float)a.G;
-  }
-  if (a.scores_tsp == nullptr) return;
-  __syncthreads();
-  for (int jj = threadIdx.x; jj < tout; jj += kThreads) {
-    const int j = j0 + r + jj;
-    if (j >= P) break;
-    float tot = 0.f;
-    for (int g = 0; g < a.Hkv; ++g) tot += g_sum[g][jj];
-    a.scores_tsp[col0 + j] = tot / (float)a.Hq;  // Eq. 2
-  }
+  pool_and_write<kTile>(a, s_head, g_sum, j0, j0 + r, min(j0 + r + tout, P), col0);
+  FKV_TICK(27);
 }
 
 hipError_t launch_stats(const ScoreArgs &a, int n_blocks, hipStream_t s) {

@@ -1,0 +1,181 @@
+// Device helpers shared by the score kernels: MFMA operand loads and the K streaming loop.
+#pragma once
+
+#include "fkv_internal.h"
+
+namespace fkv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float floatx16;
+
+constexpr int kWaves = 8;            // one wave per KV head
+constexpr int kThreads = kWaves * 64;
+constexpr int kStatsChunk = 128;     // tokens per block in k_stats
+constexpr int kTile = 128;           // tokens computed per block in k_scores (incl. pooling halo)
+constexpr int kSub = 32;             // tokens per MFMA sub-tile
+constexpr int kStageBytes = kSub * kHeadDim * 2;  // 8 KiB per wave
+constexpr float kNegBig = -1.0e30f;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ int find_seq(const SeqMap &map, int block) {
+  int b = 0;
+  while (b + 1 < map.n_seq && block >= map.blk[b + 1]) ++b;
+  return b;
+}
+
+// Orders this wave's LDS traffic (writes of one layout, reads of another) without a block barrier.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// MFMA A operand for KV group g: lane (m = lane%32, hi = lane/32) holds, for step s, the 8
+// values d = hi*64 + s*8 .. +7 of query row m (head g*G + m/8, window row m%8).  The
+// contraction index may be permuted freely as long as K uses the same permutation.
+__device__ __forceinline__ void load_q(const ScoreArgs &a, int b, int g, int lane, bf16x8 (&qa)[8]) {
+  const int m = lane & 31, hi = lane >> 5;
+  const int hl = m >> 3, w = m & 7;
+  const bool ok = hl < a.G && w < a.W;
+  const u32x4 *src = reinterpret_cast<const u32x4 *>(
+      a.q_win + (((size_t)b * a.W + (ok ? w : 0)) * a.Hq + (size_t)g * a.G + (ok ? hl : 0)) * kHeadDim + hi * 64);
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    u32x4 v = src[s];
+    if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
+    qa[s] = __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+// Streams the K rows of one KV head for `n_sub` consecutive 32-token sub-tiles starting at
+// sequence-local token `first` (tokens are clamped into [0, Lb-1] for the load; the caller masks
+// what lies outside its range).  fn(st, acc) receives the raw logits of sub-tile st:
+// acc[r] = q_row(m) . k(token first + st*32 + lane%32) with m = (r/4)*8 + (lane/32)*4 + r%4,
+// i.e. head r/4 of the group and window row (lane/32)*4 + r%4.
+template <typename F>
+__device__ __forceinline__ void stream_head(const ScoreArgs &a, const bf16x8 (&qa)[8], int tok_base, int Lb, int g,
+                                            int first, int n_sub, uint8_t *stage, int lane, F fn) {
+  const int c = lane & 15;        // 16-byte column of the 256-byte head row
+  const int tq = lane >> 4;       // token within a quad of 4 tokens per load instruction
+  const int n = lane & 31, hi = lane >> 5;
+  const uint16_t *kbase = a.k + (size_t)g * kHeadDim + c * 8;
+  const size_t tok_stride = (size_t)a.Hkv * kHeadDim;
+
+  u32x4 nxt[8];
+  auto issue = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int t = first + st * kSub + i * 4 + tq;
+      t = min(max(t, 0), Lb - 1);
+      nxt[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)(tok_base + t) * tok_stride);
+    }
+  };
+  issue(0);
+#pragma unroll 1
+  for (int st = 0; st < n_sub; ++st) {
+    wave_lds_sync();  // previous sub-tile's reads are done before the tile is overwritten
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int t = i * 4 + tq;  // token slot in the tile
+      *reinterpret_cast<u32x4 *>(stage + t * 256 + ((c ^ (t & 15)) << 4)) = nxt[i];
+    }
+    if (st + 1 < n_sub) issue(st + 1);
+    wave_lds_sync();
+    floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const u32x4 kb = *reinterpret_cast<const u32x4 *>(stage + n * 256 + (((hi * 8 + s) ^ (n & 15)) << 4));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], __builtin_bit_cast(bf16x8, kb), acc, 0, 0, 0);
+    }
+    fn(st, acc);
+  }
+}
+
+// Folds the per-lane running (max, sum) pairs of a wave's 32 softmax rows over the 32 token
+// lanes, through a wave-private LDS transpose (`scratch` >= 4480 bytes, 4-byte aligned).
+// In: mx[r], sm[r] of row m = (r/4)*8 + (lane/32)*4 + r%4 for token lane%32.
+// Out (every lane; lanes l and l+32 agree): (M, S) of row lane%32, S relative to M.
+// The summation order is fixed, so results are reproducible.
+__device__ __forceinline__ float2 fold_rows(const float (&mx)[16], const float (&sm)[16], float *scratch, int lane) {
+  const int n = lane & 31, hi = lane >> 5;
+  float *T = scratch;             // [32 rows][33]
+  float *Mrow = scratch + 32 * 33;
+  wave_lds_sync();
+#pragma unroll
+  for (int r = 0; r < 16; ++r) T[((r >> 2) * 8 + hi * 4 + (r & 3)) * 33 + n] = mx[r];
+  wave_lds_sync();
+  const int row = lane & 31, half = lane >> 5;
+  float M = kNegBig;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) M = fmaxf(M, T[row * 33 + half * 16 + j]);
+  M = fmaxf(M, __shfl_xor(M, 32));
+  if (lane < 32) Mrow[row] = M;
+  wave_lds_sync();
+  float scaled[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) scaled[r] = sm[r] * fast_exp2(mx[r] - Mrow[(r >> 2) * 8 + hi * 4 + (r & 3)]);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) T[((r >> 2) * 8 + hi * 4 + (r & 3)) * 33 + n] = scaled[r];
+  wave_lds_sync();
+  float S = 0.f;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) S += T[row * 33 + half * 16 + j];
+  S += __shfl_xor(S, 32);
+  return make_float2(M, S);
+}
+
+// Merges two (max, sum) pairs of the same softmax row (log2 domain).
+__device__ __forceinline__ float2 merge_stats(float2 x, float2 y) {
+  const float mn = fmaxf(x.x, y.x);
+  return make_float2(mn, x.y * fast_exp2(x.x - mn) + y.y * fast_exp2(y.x - mn));
+}
+
+// Pools the per-head window sums along tokens (Eq. 1), averages the heads of each KV group
+// (App. B.1) and all heads (Eq. 2) and writes the scores of the owned tokens [o0, o1).
+// s_head[h][slot] holds head h's window-summed probability of token j0 + slot, 0 outside the
+// prefix: neutral for max pooling (scores are >= 0) and the zero padding of avg pooling.
+// Slots o0 - r - j0 .. o1 + r - 1 - j0 must be filled.  Contains block barriers.
+template <int kStride>
+__device__ __forceinline__ void pool_and_write(const ScoreArgs &a, const float (*s_head)[kStride],
+                                               float (*g_sum)[kStride], int j0, int o0, int o1, int col0) {
+  const int r = a.pool_r;
+  const int own = o1 - o0;
+  const float inv_k = 1.0f / (float)(2 * r + 1), inv_g = 1.0f / (float)a.G, inv_h = 1.0f / (float)a.Hq;
+  const bool is_max = a.pool_mode == FKV_POOL_MAX;
+#pragma unroll 1
+  for (int i = threadIdx.x; i < own * a.Hkv; i += blockDim.x) {
+    const int g = i / own, jj = i - g * own;
+    const int c = o0 + jj - j0;  // slot of the pooled token
+    float gs = 0.f;
+#pragma unroll 1
+    for (int hl = 0; hl < a.G; ++hl) {
+      const float *row = s_head[g * kMaxGroup + hl] + c;
+      float p;
+      if (r == 3) {
+        const float v0 = row[-3], v1 = row[-2], v2 = row[-1], v3 = row[0], v4 = row[1], v5 = row[2], v6 = row[3];
+        p = is_max ? fmaxf(fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)), fmaxf(fmaxf(v4, v5), v6))
+                   : ((((((v0 + v1) + v2) + v3) + v4) + v5) + v6) * inv_k;
+      } else if (is_max) {
+        p = row[0];
+        for (int t = -r; t <= r; ++t) p = fmaxf(p, row[t]);
+      } else {
+        p = 0.f;
+        for (int t = -r; t <= r; ++t) p += row[t];
+        p *= inv_k;
+      }
+      gs += p;
+    }
+    g_sum[g][jj] = gs;
+    a.scores_group[(size_t)g * a.sum_p + col0 + o0 + jj] = gs * inv_g;
+  }
+  if (a.scores_tsp == nullptr) return;
+  __syncthreads();
+  for (int jj = threadIdx.x; jj < own; jj += blockDim.x) {
+    float tot = 0.f;
+    for (int g = 0; g < a.Hkv; ++g) tot += g_sum[g][jj];
+    a.scores_tsp[col0 + o0 + jj] = tot * inv_h;
+  }
+}
+
+}  // namespace fkv

@@ -2,16 +2,16 @@
 // order-preserving integer image of the fp32 scores, then an ordered compaction, so the
 // output is ascending, has exactly k entries and equal scores go to the lower index.
 //
-// One 1024-thread block per (row, sequence).  Thread t owns 32 consecutive keys of each
-// 32768-key chunk ("blocked" layout), read with 128-bit loads.  Rows of up to one chunk stay
-// in registers for the whole kernel; longer rows are re-read from L2 per pass.
-//   1. three histogram passes (11 + 11 + 10 bits, most significant first) over an LDS
-//      histogram narrow down the key T of the (k-W)-th largest prefix score; runs of equal
-//      digits inside a thread are merged before the LDS atomic (pooled scores are smooth, so
-//      neighbours mostly share a digit);
-//   2. one block-wide exclusive scan of the per-thread keep counts gives every thread its
-//      output offset; it then writes its kept indices in order: all keys > T and the first
-//      `need_eq` keys == T by index.
+// One 1024-thread block per (row, sequence).  Each thread holds 32 keys of every 32768-key
+// chunk, read with coalesced 128-bit loads.  Rows of up to one chunk stay in registers for
+// the whole kernel; longer rows are re-read from L2 per pass.
+//   1. the row's smallest and largest key bound the search interval [lo, lo + 2^s); histogram
+//      passes of up to 11 bits of (key - lo), most significant first, narrow it down to the key
+//      T of the (k-W)-th largest prefix score.  Taking digits relative to the row's own range
+//      spreads the keys over the 2048 LDS bins (fp32 exponents would crowd them into a few
+//      dozen) and makes a constant row cost no pass at all;
+//   2. wave ballots plus one LDS exchange of wave totals give every kept key its output
+//      offset in index order: all keys > T and the first `need_eq` keys == T by index.
 #include "fkv_internal.h"
 
 namespace fkv {
@@ -30,13 +30,18 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Keys of virtual positions v0 .. v0+31 of the row, where position v holds score v - mis
-// (`base` = row pointer - mis is 16-byte aligned).  Positions outside [mis, mis+P) get key 0.
-__device__ __forceinline__ void load_keys(const float *base, int mis, int P, int v0, uint32_t (&key)[kKpt]) {
+// Key layout of a 32768-key chunk: wave w owns virtual positions [2048 w, 2048 w + 2048); its
+// q-th 128-bit load covers positions 2048 w + 256 q + 4 lane + {0..3}, so every load
+// instruction reads 1 KiB of consecutive memory.  Position v holds score v - mis (`base` = row
+// pointer - mis is 16-byte aligned); positions outside [mis, mis+P) get key 0.
+__device__ __forceinline__ int slot_pos(int wave, int lane, int q) { return wave * 2048 + q * 256 + lane * 4; }
+
+__device__ __forceinline__ void load_keys(const float *base, int mis, int P, int v_chunk, int wave, int lane,
+                                          uint32_t (&key)[kKpt]) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
   for (int q = 0; q < kKpt / 4; ++q) {
-    const int v = v0 + 4 * q;
+    const int v = v_chunk + slot_pos(wave, lane, q);
     if (v >= mis && v + 3 < mis + P) {
       const f32x4 f = *reinterpret_cast<const f32x4 *>(base + v);
       key[4 * q + 0] = order_key(f[0]);
@@ -54,39 +59,60 @@ __device__ __forceinline__ void load_keys(const float *base, int mis, int P, int
 }
 
 template <bool kResident>
-__device__ __forceinline__ void select_row(const float *sc, int P, int kp, int W, int32_t *out, uint32_t *hist,
+__device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32_t *out, uint32_t *hist,
                                            uint32_t *wsum, uint32_t *bcast) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int mis = (int)((reinterpret_cast<uintptr_t>(sc) >> 2) & 3);
   const float *base = sc - mis;
   const int n_chunks = kResident ? 1 : (P + mis + kChunk - 1) / kChunk;
   uint32_t key[kKpt];
-  if (kResident) load_keys(base, mis, P, tid * kKpt, key);
+  FKV_TICK(0);
 
-  uint32_t prefix = 0, mask = 0, remaining = (uint32_t)kp;
-  uint32_t need_eq = 0;
-  bool done = false;
-  for (int pass = 0; pass < 3 && !done; ++pass) {
-    const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-    const uint32_t nb = pass == 2 ? 1024u : 2048u;
+  // ---- key range of the row: the radix digits are taken relative to the smallest key, so
+  // the bins spread over the values the row really holds instead of over fp32's exponent
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  for (int ch = 0; ch < n_chunks; ++ch) {
+    load_keys(base, mis, P, ch * kChunk, wave, lane, key);
+#pragma unroll
+    for (int e = 0; e < kKpt; ++e) {
+      kmax = max(kmax, key[e]);
+      kmin = min(kmin, key[e] - 1u);  // key 0 (no element) wraps to the largest value
+    }
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off));
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off));
+  }
+  if (lane == 0) { wsum[wave] = kmin; wsum[kSelWaves + wave] = kmax; }
+  __syncthreads();
+  for (int w = 0; w < kSelWaves; ++w) {
+    kmin = min(kmin, wsum[w]);
+    kmax = max(kmax, wsum[kSelWaves + w]);
+  }
+  kmin += 1u;
+
+  FKV_TICK(1);
+  // ---- narrow [lo, lo + 2^s) down to the key T of the kp-th largest score
+  uint32_t lo = kmin, remaining = (uint32_t)kp, need_eq = remaining;
+  int s = (kmax == kmin) ? 0 : 32 - __clz(kmax - kmin);  // kmax - kmin < 2^s
+  while (s > 0) {
+    const int bits = min(11, s);
+    const int shift = s - bits;
+    const uint32_t span = (s >= 32) ? 0xFFFFFFFFu : ((1u << s) - 1u);  // candidates: key - lo <= span
+    __syncthreads();  // wsum / hist / bcast readers of the previous round are done
     for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
     __syncthreads();
     for (int ch = 0; ch < n_chunks; ++ch) {
-      if (!kResident) load_keys(base, mis, P, ch * kChunk + tid * kKpt, key);
-      uint32_t cur = 0, cnt = 0;
+      if (!kResident) load_keys(base, mis, P, ch * kChunk, wave, lane, key);
 #pragma unroll
       for (int e = 0; e < kKpt; ++e) {
-        const uint32_t kk = key[e];
-        if (kk != 0u && (kk & mask) == prefix) {
-          const uint32_t bin = (kk >> shift) & (nb - 1u);
-          if (bin != cur && cnt) { atomicAdd(&hist[cur], cnt); cnt = 0; }
-          cur = bin;
-          ++cnt;
-        }
+        const uint32_t rel = key[e] - lo;  // keys below lo (and key 0) wrap far above span
+        if (key[e] >= lo && rel <= span) atomicAdd(&hist[rel >> shift], 1u);
       }
-      if (cnt) atomicAdd(&hist[cur], cnt);
     }
     __syncthreads();
+    FKV_TICK(8 + 2 * (s > 22 ? 0 : (s > 11 ? 1 : 2)));
     // thread owns bins 2*tid, 2*tid+1; suffix sums from the top bin down
     const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
     const uint32_t mine = h0 + h1;
@@ -105,72 +131,89 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int W
       const uint32_t digit = 2 * tid + (top ? 1 : 0);
       const uint32_t in_bin = top ? h1 : h0;
       const uint32_t rem = remaining - above - (top ? 0u : h1);
-      bcast[0] = prefix | (digit << shift);
+      bcast[0] = lo + (digit << shift);
       bcast[1] = rem;
       bcast[2] = (in_bin == rem) ? 1u : 0u;  // the whole bin is kept: no need to refine further
     }
     __syncthreads();
-    prefix = bcast[0];
+    lo = bcast[0];
     remaining = bcast[1];
-    mask |= (nb - 1u) << shift;
-    if (bcast[2]) { done = true; need_eq = 0xFFFFFFFFu; } else need_eq = remaining;
-    // (bcast is rewritten only after the next pass's two barriers)
+    need_eq = remaining;
+    s = shift;
+    if (bcast[2]) { need_eq = 0xFFFFFFFFu; break; }
   }
   // keep key > T, and key == T while fewer than need_eq equal keys came before it.  When a whole
   // bin is kept, T is the smallest key the bin could hold and every key == T is kept.
-  const uint32_t T = prefix;
+  const uint32_t T = lo;
+  FKV_TICK(2);
 
+  // ---- ordered compaction.  Index order inside a wave is (q, lane, e); ballots give each lane
+  // the number of kept keys of lower lanes per q, a single LDS exchange the totals of lower waves.
+  const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   uint32_t run_gt = 0, run_eq = 0;
   for (int ch = 0; ch < n_chunks; ++ch) {
-    if (!kResident) load_keys(base, mis, P, ch * kChunk + tid * kKpt, key);
-    uint32_t cg = 0, ce = 0;
+    if (!kResident) load_keys(base, mis, P, ch * kChunk, wave, lane, key);
+    uint32_t gt_mask = 0, eq_mask = 0;
 #pragma unroll
     for (int e = 0; e < kKpt; ++e) {
-      cg += (key[e] > T) ? 1u : 0u;
-      ce += (key[e] == T) ? 1u : 0u;
+      gt_mask |= (key[e] > T) ? (1u << e) : 0u;
+      eq_mask |= (key[e] == T) ? (1u << e) : 0u;
     }
-    // block-wide exclusive scan of (cg, ce); both fit 16 bits within a chunk
-    const uint32_t packed = cg | (ce << 16);
-    uint32_t inc = packed;
+    // wave totals first (packed: low 16 bits gt, high 16 bits eq), exchanged through LDS
+    uint32_t wave_tot = (uint32_t)__popc(gt_mask) | ((uint32_t)__popc(eq_mask) << 16);
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t v = __shfl_up(inc, off);
-      if (lane >= off) inc += v;
-    }
+    for (int off = 1; off < 64; off <<= 1) wave_tot += (uint32_t)__shfl_xor((int)wave_tot, off);
     __syncthreads();  // wsum is free (previous readers are past their loop)
-    if (lane == 63) wsum[wave] = inc;
+    if (lane == 0) wsum[wave] = wave_tot;
     __syncthreads();
-    uint32_t before = inc - packed, total = 0;
+    uint32_t before_w = 0, total = 0;
     for (int w = 0; w < kSelWaves; ++w) {
       const uint32_t v = wsum[w];
-      if (w < wave) before += v;
+      if (w < wave) before_w += v;
       total += v;
     }
-    uint32_t gt_before = run_gt + (before & 0xFFFFu);
-    uint32_t eq_before = run_eq + (before >> 16);
-    const int i0 = ch * kChunk + tid * kKpt - mis;
-    if (cg | ce) {
+    uint32_t gt_q = run_gt + (before_w & 0xFFFFu), eq_q = run_eq + (before_w >> 16);  // kept before this q
+    const int i_chunk = ch * kChunk - mis;
 #pragma unroll
-      for (int e = 0; e < kKpt; ++e) {
-        const uint32_t kk = key[e];
-        if (kk > T) {
-          out[gt_before + min(eq_before, need_eq)] = i0 + e;
-          ++gt_before;
-        } else if (kk == T) {
-          if (eq_before < need_eq) out[gt_before + eq_before] = i0 + e;
-          ++eq_before;
+    for (int q = 0; q < kKpt / 4; ++q) {
+      const uint32_t gq = (gt_mask >> (4 * q)) & 15u, eqq = (eq_mask >> (4 * q)) & 15u;
+      uint32_t lane_gt = 0, lane_eq = 0, tot_gt = 0, tot_eq = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint64_t bg = __ballot((gq >> e) & 1u);
+        const uint64_t be = __ballot((eqq >> e) & 1u);
+        lane_gt += (uint32_t)__popcll(bg & lower);
+        lane_eq += (uint32_t)__popcll(be & lower);
+        tot_gt += (uint32_t)__popcll(bg);
+        tot_eq += (uint32_t)__popcll(be);
+      }
+      if (gq | eqq) {
+        uint32_t gt_before = gt_q + lane_gt;
+        uint32_t eq_before = eq_q + lane_eq;
+        const int i0 = i_chunk + slot_pos(wave, lane, q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if ((gq >> e) & 1u) {
+            out[gt_before + min(eq_before, need_eq)] = i0 + e;
+            ++gt_before;
+          } else if ((eqq >> e) & 1u) {
+            if (eq_before < need_eq) out[gt_before + eq_before] = i0 + e;
+            ++eq_before;
+          }
         }
       }
+      gt_q += tot_gt;
+      eq_q += tot_eq;
     }
     run_gt += total & 0xFFFFu;
     run_eq += total >> 16;
   }
-  (void)W;
+  FKV_TICK(3);
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
   __shared__ uint32_t hist[kBins];
-  __shared__ uint32_t wsum[kSelWaves];
+  __shared__ uint32_t wsum[2 * kSelWaves];
   __shared__ uint32_t bcast[4];
 
   int row = blockIdx.x;
@@ -188,9 +231,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
   if ((int)threadIdx.x < a.W) out[kp + threadIdx.x] = P + threadIdx.x;  // window tokens are always kept
   if (kp <= 0) return;
   if (P + 3 <= kChunk)
-    select_row<true>(sc, P, kp, a.W, out, hist, wsum, bcast);
+    select_row<true>(sc, P, kp, out, hist, wsum, bcast);
   else
-    select_row<false>(sc, P, kp, a.W, out, hist, wsum, bcast);
+    select_row<false>(sc, P, kp, out, hist, wsum, bcast);
 }
 
 hipError_t launch_select(const SelectArgs &a, hipStream_t s) {

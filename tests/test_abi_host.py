@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, name), name
     assert sorted(fk.EXPORTS) == declared
     assert lib.fkv_version() >= 100
-    assert lib.fkv_profile_kernels() == 5
+    assert lib.fkv_profile_kernels() == 6
     assert lib.fkv_strerror(fk.FKV_EALIGN).decode().startswith("device pointer")
 
 
@@ -126,6 +126,7 @@ def test_entry_points_validate_before_touching_the_context(lib):
     assert lib.fkv_compress_kv(None, ctypes.byref(s), p16, p16, p16, k, p16, p16, p16,
                                None, 0, None, None, None, None) == fk.FKV_ENULL                   # ctx
     assert lib.fkv_destroy(None) == fk.FKV_ENULL
+    assert lib.fkv_set_score_path(None, 0) == fk.FKV_ENULL and lib.fkv_query_error(None, None) == fk.FKV_ENULL
 
 
 def test_workspace_bytes(lib):

@@ -15,11 +15,12 @@ pytestmark = pytest.mark.gpu
 W = 8
 
 
-def _full_check(L, k_tsp, budget, pool_mode, seed):
+def _full_check(L, k_tsp, budget, pool_mode, seed, score_path=0):
     t0 = time.time()
     s = wl.make_sequence(seed, L)
     print("  inputs generated in %.1fs" % (time.time() - t0), flush=True)
     ctx = fk.Context(max_total_tokens=L, max_seqs=1)
+    ctx.fkv_set_score_path(score_path)
     shape = fk.make_shape(L, pool_mode=pool_mode)
     q, k, v, x = dev_bf16(s["q_win"]), dev_bf16(s["k"]), dev_bf16(s["v"]), dev_bf16(s["x"])
     out = ctx.fkv_compress_kv(shape, q, k, v, budget, x=x, k_tsp_per_seq=k_tsp)
@@ -47,13 +48,20 @@ def _full_check(L, k_tsp, budget, pool_mode, seed):
     recall = np.isin(s["heavy"], idx_tsp).mean()
     print("  max rel err group %.2e tsp %.2e; tolerance-band flips %d; heavy recall %.2f" % (e1, e2, flips, recall),
           flush=True)
+    assert ctx.fkv_query_error() == 0
     ctx.close()
 
 
 @pytest.mark.parametrize("pool_mode", ["avg", "max"])
 def test_config2_32k(pool_mode):
+    # default path: the single-pass score kernel (the configuration bench.py times)
     print("case: config2 L=32768 %s" % pool_mode, flush=True)
     _full_check(32768, 6554, 2048, pool_mode, seed=0)
+
+
+def test_config2_32k_two_pass():
+    print("case: config2 L=32768 avg, two-pass score kernels", flush=True)
+    _full_check(32768, 6554, 2048, "avg", seed=1, score_path=1)
 
 
 def test_config3_128k():

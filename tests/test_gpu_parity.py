@@ -11,10 +11,15 @@ from parity import assert_index_set, assert_scores_close, dev_bf16, host_bits
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def ctx():
+@pytest.fixture(scope="module", params=["auto", "two_pass"])
+def ctx(request):
+    """Every case runs twice: with the default score path (the single-pass resident-grid kernel
+    whenever the batch fits, which all cases of this file do) and with the two-pass kernels."""
     c = fk.Context(max_total_tokens=140000, max_seqs=16)
+    c.fkv_set_score_path(0 if request.param == "auto" else 1)
+    print("score path:", request.param, flush=True)
     yield c
+    assert c.fkv_query_error() == 0
     c.close()
 
 
@@ -285,6 +290,27 @@ def test_deterministic(ctx):
         for n in a:
             assert torch.equal(a[n].view(torch.int16) if a[n].dtype == torch.bfloat16 else a[n],
                                b[n].view(torch.int16) if b[n].dtype == torch.bfloat16 else b[n]), n
+
+
+def test_single_pass_path_is_taken_and_rejects_oversize(ctx):
+    print("case: forced single-pass path", flush=True)
+    c2 = fk.Context(max_total_tokens=140000, max_seqs=4)
+    c2.fkv_set_score_path(2)
+    s = wl.make_sequence(6, 5000, n_heavy=20, with_v=False, with_x=False)
+    shape = fk.make_shape(5000)
+    sg, st = c2.fkv_score_window(shape, dev_bf16(s["q_win"]), dev_bf16(s["k"]))
+    rg, rt = _oracle_batch([s], 7, "max", precision="f64")
+    assert_scores_close(sg.cpu().numpy(), rg, "scores_group")
+    assert_scores_close(st.cpu().numpy(), rt, "scores_tsp")
+    big = fk.make_shape(131072)
+    k = torch.zeros((131072, 8, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fk.FkvError) as ei:
+        c2.fkv_score_window(big, dev_bf16(s["q_win"]), k)
+    assert ei.value.status == fk.FKV_EUNSUPPORTED
+    with pytest.raises(fk.FkvError):
+        c2.fkv_set_score_path(3)
+    assert c2.fkv_query_error() == 0
+    c2.close()
 
 
 def test_chain_small(ctx):
