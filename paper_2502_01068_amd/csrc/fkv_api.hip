@@ -283,7 +283,10 @@ int enqueue_gather(fkv_ctx *ctx, GatherArgs &g, const Resolved &r, hipStream_t s
 }  // namespace
 
 #ifdef FKV_TIMING
-namespace fkv { __device__ unsigned long long fkv_ticks[64]; }
+namespace fkv { __device__ unsigned long long fkv_ticks[64]; __device__ unsigned long long fkv_block_ticks[1024 * 4]; }
+extern "C" int fkv_debug_read_block_ticks(unsigned long long *out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(fkv::fkv_block_ticks), sizeof(unsigned long long) * 4096);
+}
 extern "C" int fkv_debug_read_ticks(unsigned long long *out) {
   return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(fkv::fkv_ticks), sizeof(unsigned long long) * 64);
 }

@@ -141,7 +141,7 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
           const float e = fast_exp2(acc[hl * 4 + rr] * a.scale_log2e - cst[hl * 4 + rr]);
           sum += (hi * 4 + rr < a.W) ? e : 0.f;
         }
-        sum += __shfl_xor(sum, 32);  // other half of the window rows
+        sum = add_across_halves(sum);  // other half of the window rows
 #pragma unroll
         for (int q = 0; q < kNSub; ++q)
           if (q == st) hsum[q][hl] = sum;

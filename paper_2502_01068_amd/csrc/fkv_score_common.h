@@ -96,7 +96,9 @@ __device__ __forceinline__ void stream_head(const ScoreArgs &a, const bf16x8 (&q
 // lanes, through a wave-private LDS transpose (`scratch` >= 4480 bytes, 4-byte aligned).
 // In: mx[r], sm[r] of row m = (r/4)*8 + (lane/32)*4 + r%4 for token lane%32.
 // Out (every lane; lanes l and l+32 agree): (M, S) of row lane%32, S relative to M.
+// On return scratch[32*33 + m] still holds M of row m (kFoldMaxOffset floats into scratch).
 // The summation order is fixed, so results are reproducible.
+constexpr int kFoldMaxOffset = 32 * 33;
 __device__ __forceinline__ float2 fold_rows(const float (&mx)[16], const float (&sm)[16], float *scratch, int lane) {
   const int n = lane & 31, hi = lane >> 5;
   float *T = scratch;             // [32 rows][33]
@@ -125,6 +127,13 @@ __device__ __forceinline__ float2 fold_rows(const float (&mx)[16], const float (
   return make_float2(M, S);
 }
 
+// x(lane) + x(lane ^ 32) in every lane, low half first (one VALU lane swap, no LDS round trip).
+__device__ __forceinline__ float add_across_halves(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // Merges two (max, sum) pairs of the same softmax row (log2 domain).
 __device__ __forceinline__ float2 merge_stats(float2 x, float2 y) {
   const float mn = fmaxf(x.x, y.x);
@@ -143,31 +152,33 @@ __device__ __forceinline__ void pool_and_write(const ScoreArgs &a, const float (
   const int own = o1 - o0;
   const float inv_k = 1.0f / (float)(2 * r + 1), inv_g = 1.0f / (float)a.G, inv_h = 1.0f / (float)a.Hq;
   const bool is_max = a.pool_mode == FKV_POOL_MAX;
+  const int lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
+  for (int g = threadIdx.x >> 6; g < a.Hkv; g += n_waves) {  // one wave per KV group
 #pragma unroll 1
-  for (int i = threadIdx.x; i < own * a.Hkv; i += blockDim.x) {
-    const int g = i / own, jj = i - g * own;
-    const int c = o0 + jj - j0;  // slot of the pooled token
-    float gs = 0.f;
+    for (int jj = lane; jj < own; jj += 64) {
+      const int c = o0 + jj - j0;  // slot of the pooled token
+      float gs = 0.f;
 #pragma unroll 1
-    for (int hl = 0; hl < a.G; ++hl) {
-      const float *row = s_head[g * kMaxGroup + hl] + c;
-      float p;
-      if (r == 3) {
-        const float v0 = row[-3], v1 = row[-2], v2 = row[-1], v3 = row[0], v4 = row[1], v5 = row[2], v6 = row[3];
-        p = is_max ? fmaxf(fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)), fmaxf(fmaxf(v4, v5), v6))
-                   : ((((((v0 + v1) + v2) + v3) + v4) + v5) + v6) * inv_k;
-      } else if (is_max) {
-        p = row[0];
-        for (int t = -r; t <= r; ++t) p = fmaxf(p, row[t]);
-      } else {
-        p = 0.f;
-        for (int t = -r; t <= r; ++t) p += row[t];
-        p *= inv_k;
+      for (int hl = 0; hl < a.G; ++hl) {
+        const float *row = s_head[g * kMaxGroup + hl] + c;
+        float p;
+        if (r == 3) {
+          const float v0 = row[-3], v1 = row[-2], v2 = row[-1], v3 = row[0], v4 = row[1], v5 = row[2], v6 = row[3];
+          p = is_max ? fmaxf(fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)), fmaxf(fmaxf(v4, v5), v6))
+                     : ((((((v0 + v1) + v2) + v3) + v4) + v5) + v6) * inv_k;
+        } else if (is_max) {
+          p = row[0];
+          for (int t = -r; t <= r; ++t) p = fmaxf(p, row[t]);
+        } else {
+          p = 0.f;
+          for (int t = -r; t <= r; ++t) p += row[t];
+          p *= inv_k;
+        }
+        gs += p;
       }
-      gs += p;
+      g_sum[g][jj] = gs;
+      a.scores_group[(size_t)g * a.sum_p + col0 + o0 + jj] = gs * inv_g;
     }
-    g_sum[g][jj] = gs;
-    a.scores_group[(size_t)g * a.sum_p + col0 + o0 + jj] = gs * inv_g;
   }
   if (a.scores_tsp == nullptr) return;
   __syncthreads();

@@ -85,8 +85,9 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   const bool has_group = g < a.Hkv;
 
   FKV_TICK(32);
+  FKV_BTICK(0);
   // ---- phase 1: logits into registers, running statistics of the owned tokens
-  float z[kFusedSub][16];
+  float z[kFusedSub][16], mloc[16];
   float2 ms = make_float2(kNegBig, 0.f);
   if (has_group) {
     bf16x8 qa[8];
@@ -105,19 +106,33 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
 #pragma unroll
         for (int t = 0; t < kFusedSub; ++t)
           if (t == st) z[t][q] = zz;
-        const float zs = ok ? zz : kNegBig;
-        const float d = zs - mx[q];
+        // running reference = max over every computed logit (counted or not), so that
+        // 2^(z - reference) <= 1 for all of them; only counted keys enter the sum
+        const float d = zz - mx[q];
         const float e = fast_exp2(-fabsf(d));
-        sm[q] = d > 0.f ? sm[q] * e + 1.f : sm[q] + (ok ? e : 0.f);
-        mx[q] = fmaxf(mx[q], zs);
+        const float one = ok ? 1.f : 0.f;
+        sm[q] = d > 0.f ? sm[q] * e + one : sm[q] + one * e;
+        mx[q] = fmaxf(mx[q], zz);
       }
     });
     FKV_TICK(33);
     ms = fold_rows(mx, sm, reinterpret_cast<float *>(stage), lane);
     if (lane < 32) st_coherent(f.bpartial + (size_t)(g * kRowsPerGroup + lane) * f.bpartial_stride + blockIdx.x, ms);
+    // While the exchange is in flight: turn the kept logits into 2^(z - block reference).  The
+    // global normaliser then costs one multiply per value instead of an exponential.
+    const float *mrow = reinterpret_cast<const float *>(stage) + kFoldMaxOffset;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) mloc[q] = mrow[(q >> 2) * 8 + hi * 4 + (q & 3)];
+#pragma unroll
+    for (int st = 0; st < kFusedSub; ++st)
+      if (st < n_sub) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) z[st][q] = fast_exp2(z[st][q] - mloc[q]);
+      }
   }
 
   FKV_TICK(34);
+  FKV_BTICK(1);
   // ---- phase 2: grid-wide fold of the row statistics
   const int cl_local = local / kClusterSize;
   const int cluster = f.cl0[b] + cl_local;
@@ -162,6 +177,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   __syncthreads();
   const bool grid_ok = flag_lds[1] != 0u;
   FKV_TICK(37);
+  FKV_BTICK(2);
   FKV_TICK(38);
 
   if (grid_ok && has_group) {
@@ -191,9 +207,9 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
 
   // ---- phase 3: probabilities from the kept logits, window sums into LDS
   if (grid_ok && has_group) {
-    float cst[16];
+    float fac[16];  // 2^(block reference - global log-sum-exp) per row
 #pragma unroll
-    for (int q = 0; q < 16; ++q) cst[q] = cst_lds[wave][(q >> 2) * 8 + hi * 4 + (q & 3)];
+    for (int q = 0; q < 16; ++q) fac[q] = fast_exp2(mloc[q] - cst_lds[wave][(q >> 2) * 8 + hi * 4 + (q & 3)]);
 #pragma unroll
     for (int st = 0; st < kFusedSub; ++st) {
       if (st < n_sub) {
@@ -203,11 +219,8 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
         for (int hl = 0; hl < 4; ++hl) {
           float sum = 0.f;
 #pragma unroll
-          for (int rr = 0; rr < 4; ++rr) {
-            const float e = fast_exp2(z[st][hl * 4 + rr] - cst[hl * 4 + rr]);
-            sum += (hi * 4 + rr < a.W) ? e : 0.f;
-          }
-          sum += __shfl_xor(sum, 32);  // other half of the window rows
+          for (int rr = 0; rr < 4; ++rr) sum += (hi * 4 + rr < a.W) ? z[st][hl * 4 + rr] * fac[hl * 4 + rr] : 0.f;
+          sum = add_across_halves(sum);  // other half of the window rows
           if (hi == 0 && hl < a.G) s_head[g * kMaxGroup + hl][st * kSub + n] = inb ? sum : 0.f;
         }
       }
@@ -217,6 +230,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   FKV_TICK(40);
   if (grid_ok) pool_and_write<kFusedSlots>(a, s_head, g_sum, c0, o0, o1, tok_base - b * a.W);
   FKV_TICK(41);
+  FKV_BTICK(3);
 
   // ---- leave the grid: the last block out re-arms the counters for the next launch
   if (threadIdx.x == 0) {

@@ -10,8 +10,9 @@
 //      T of the (k-W)-th largest prefix score.  Taking digits relative to the row's own range
 //      spreads the keys over the 2048 LDS bins (fp32 exponents would crowd them into a few
 //      dozen) and makes a constant row cost no pass at all;
-//   2. wave ballots plus one LDS exchange of wave totals give every kept key its output
-//      offset in index order: all keys > T and the first `need_eq` keys == T by index.
+//   2. a scan of the per-item keep counts (in-wave through an LDS table, across waves through
+//      wave totals) gives every kept key its output offset in index order: all keys > T and
+//      the first `need_eq` keys == T by index.
 #include "fkv_internal.h"
 
 namespace fkv {
@@ -58,9 +59,15 @@ __device__ __forceinline__ void load_keys(const float *base, int mis, int P, int
   }
 }
 
+__device__ __forceinline__ void wave_sync_lds() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <bool kResident>
 __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32_t *out, uint32_t *hist,
-                                           uint32_t *wsum, uint32_t *bcast) {
+                                           uint32_t *wsum, uint32_t *bcast, uint32_t *scan_tbl) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int mis = (int)((reinterpret_cast<uintptr_t>(sc) >> 2) & 3);
   const float *base = sc - mis;
@@ -147,9 +154,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   const uint32_t T = lo;
   FKV_TICK(2);
 
-  // ---- ordered compaction.  Index order inside a wave is (q, lane, e); ballots give each lane
-  // the number of kept keys of lower lanes per q, a single LDS exchange the totals of lower waves.
-  const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  // ---- ordered compaction.  Index order inside a wave is (q, lane, e).
   uint32_t run_gt = 0, run_eq = 0;
   for (int ch = 0; ch < n_chunks; ++ch) {
     if (!kResident) load_keys(base, mis, P, ch * kChunk, wave, lane, key);
@@ -159,11 +164,42 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
       gt_mask |= (key[e] > T) ? (1u << e) : 0u;
       eq_mask |= (key[e] == T) ? (1u << e) : 0u;
     }
-    // wave totals first (packed: low 16 bits gt, high 16 bits eq), exchanged through LDS
-    uint32_t wave_tot = (uint32_t)__popc(gt_mask) | ((uint32_t)__popc(eq_mask) << 16);
+    // Kept counts per (q, lane) item, packed (low 16 bits: keys > T, high 16 bits: keys == T).
+    // Index order inside the wave is item order q*64 + lane; lane l scans items 8l .. 8l+7 from a
+    // wave-private LDS table, the 64 lanes scan their sums, and the table is overwritten with the
+    // exclusive prefix of every item.
+    uint32_t *tbl = scan_tbl + wave * 512;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) wave_tot += (uint32_t)__shfl_xor((int)wave_tot, off);
-    __syncthreads();  // wsum is free (previous readers are past their loop)
+    for (int q = 0; q < kKpt / 4; ++q)
+      tbl[q * 64 + lane] = (uint32_t)__popc((gt_mask >> (4 * q)) & 15u) | ((uint32_t)__popc((eq_mask >> (4 * q)) & 15u) << 16);
+    wave_sync_lds();
+    uint32_t item[8];
+    {
+      const u32x4 a0 = *reinterpret_cast<const u32x4 *>(tbl + 8 * lane);
+      const u32x4 a1 = *reinterpret_cast<const u32x4 *>(tbl + 8 * lane + 4);
+      item[0] = a0[0]; item[1] = a0[1]; item[2] = a0[2]; item[3] = a0[3];
+      item[4] = a1[0]; item[5] = a1[1]; item[6] = a1[2]; item[7] = a1[3];
+    }
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mine += item[i];
+    uint32_t inc = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t v = (uint32_t)__shfl_up((int)inc, off);
+      if (lane >= off) inc += v;
+    }
+    const uint32_t wave_tot = (uint32_t)__shfl((int)inc, 63);
+    uint32_t pre = inc - mine;
+    wave_sync_lds();
+    {
+      u32x4 b0, b1;
+      b0[0] = pre; pre += item[0]; b0[1] = pre; pre += item[1]; b0[2] = pre; pre += item[2]; b0[3] = pre; pre += item[3];
+      b1[0] = pre; pre += item[4]; b1[1] = pre; pre += item[5]; b1[2] = pre; pre += item[6]; b1[3] = pre;
+      *reinterpret_cast<u32x4 *>(tbl + 8 * lane) = b0;
+      *reinterpret_cast<u32x4 *>(tbl + 8 * lane + 4) = b1;
+    }
+    __syncthreads();  // wsum is free (previous readers are past their loop); tables are complete
     if (lane == 0) wsum[wave] = wave_tot;
     __syncthreads();
     uint32_t before_w = 0, total = 0;
@@ -172,24 +208,15 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
       if (w < wave) before_w += v;
       total += v;
     }
-    uint32_t gt_q = run_gt + (before_w & 0xFFFFu), eq_q = run_eq + (before_w >> 16);  // kept before this q
+    const uint32_t gt0 = run_gt + (before_w & 0xFFFFu), eq0 = run_eq + (before_w >> 16);
     const int i_chunk = ch * kChunk - mis;
 #pragma unroll
     for (int q = 0; q < kKpt / 4; ++q) {
       const uint32_t gq = (gt_mask >> (4 * q)) & 15u, eqq = (eq_mask >> (4 * q)) & 15u;
-      uint32_t lane_gt = 0, lane_eq = 0, tot_gt = 0, tot_eq = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint64_t bg = __ballot((gq >> e) & 1u);
-        const uint64_t be = __ballot((eqq >> e) & 1u);
-        lane_gt += (uint32_t)__popcll(bg & lower);
-        lane_eq += (uint32_t)__popcll(be & lower);
-        tot_gt += (uint32_t)__popcll(bg);
-        tot_eq += (uint32_t)__popcll(be);
-      }
       if (gq | eqq) {
-        uint32_t gt_before = gt_q + lane_gt;
-        uint32_t eq_before = eq_q + lane_eq;
+        const uint32_t pq = tbl[q * 64 + lane];
+        uint32_t gt_before = gt0 + (pq & 0xFFFFu);
+        uint32_t eq_before = eq0 + (pq >> 16);
         const int i0 = i_chunk + slot_pos(wave, lane, q);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -202,9 +229,8 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
           }
         }
       }
-      gt_q += tot_gt;
-      eq_q += tot_eq;
     }
+    __syncthreads();  // the tables are rewritten by the next chunk
     run_gt += total & 0xFFFFu;
     run_eq += total >> 16;
   }
@@ -213,6 +239,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
 
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
   __shared__ uint32_t hist[kBins];
+  __shared__ __attribute__((aligned(16))) uint32_t scan_tbl[kSelWaves * 512];
   __shared__ uint32_t wsum[2 * kSelWaves];
   __shared__ uint32_t bcast[4];
 
@@ -231,9 +258,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
   if ((int)threadIdx.x < a.W) out[kp + threadIdx.x] = P + threadIdx.x;  // window tokens are always kept
   if (kp <= 0) return;
   if (P + 3 <= kChunk)
-    select_row<true>(sc, P, kp, out, hist, wsum, bcast);
+    select_row<true>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
   else
-    select_row<false>(sc, P, kp, out, hist, wsum, bcast);
+    select_row<false>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
 }
 
 hipError_t launch_select(const SelectArgs &a, hipStream_t s) {
