@@ -40,12 +40,70 @@ def kernel_algorithmic_bytes(L, k_tsp, budget, Hq=32, Hkv=8, d=128, hidden=4096,
     }
 
 
+def run_chain(args):
+    """Config 5: the selection work of a whole 32-layer prefill (Algorithm 1) at L = 32768.
+    Layers 0-14 compress K/V of the full context, layer 15 (the TSP layer) also selects and
+    gathers the propagated hidden rows, layers 16-31 score and compress the 6554 propagated
+    tokens.  Every layer has its own seeded inputs.  Prints one JSON line (time, lower is better)."""
+    import torch
+    from paper_2502_01068_amd import binding as fk
+    from paper_2502_01068_amd import workloads as wl
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import dev_bf16
+
+    L, budget, n_layers, tsp_layer = 32768, 2048, 32, 15
+    k_tsp = wl.round_half_up(0.2 * L)
+    torch.cuda.set_device(0)
+    ctx = fk.Context(max_total_tokens=L, max_seqs=1, device=0)
+    layers = []
+    for layer in range(n_layers):
+        Lc = L if layer <= tsp_layer else k_tsp
+        h = wl.make_sequence(args.seed, Lc, layer=layer, with_x=(layer == tsp_layer))
+        d = {n: dev_bf16(h[n]) for n in ("q_win", "k", "v")}
+        d["x"] = dev_bf16(h["x"]) if layer == tsp_layer else None
+        d["shape"] = fk.make_shape(Lc, pool_mode=args.pool)
+        d["L"] = Lc
+        d["out"] = None
+        layers.append(d)
+
+    def chain():
+        for d in layers:
+            d["out"] = ctx.fkv_compress_kv(d["shape"], d["q_win"], d["k"], d["v"], min(budget, d["L"]), x=d["x"],
+                                           k_tsp_per_seq=k_tsp if d["x"] is not None else None, out=d["out"])
+
+    for _ in range(max(args.warmup // 4, 2)):
+        chain()
+    torch.cuda.synchronize()
+    n = max(args.steps // 10, 5)
+    t0 = time.perf_counter()
+    for _ in range(n):
+        chain()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / n
+    tokens = (tsp_layer + 1) * L + (n_layers - tsp_layer - 1) * k_tsp
+    total_bytes = sum(wl.algorithmic_bytes(d["L"], k_tsp if d["x"] is not None else 0, min(budget, d["L"]))
+                      for d in layers)
+    print(json.dumps({
+        "metric": "end-to-end selection time of the 32-layer chain at L=32768", "value": ms, "unit": "ms",
+        "n_gpus": 1, "steps": n, "warmup": max(args.warmup // 4, 2), "ms_per_step": ms, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 inputs, fp32 accumulate and scores, int32 indices",
+        "data": "synthetic (seeded N(0,1) bf16 + 1% planted heavy keys, independent per layer)",
+        "config": {"workload": "config5_chain: 32 layers, TSP layer 15, L=32768 -> 6554, kv budget 2048, pool %s 7" % args.pool},
+        "path": {"token_layers": tokens, "token_layers_per_s": tokens / (ms * 1e-3), "algorithmic_bytes": total_bytes,
+                 "achieved_GBps": total_bytes / (ms * 1e-3) / 1e9,
+                 "frac_of_peak": total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "context": {"paper": "the paper's token-importance estimation costs 0.04 s per 32K prefill on one A100 SXM "
+                             "(App. D.4) - another machine and software stack, context only"}}))
+    assert ctx.fkv_query_error() == 0
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="config2_L32768", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="config2_L32768", choices=sorted(WORKLOADS) + ["config5_chain"])
     ap.add_argument("--pool", default="avg", choices=["avg", "max"])
     ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated over the steps")
     ap.add_argument("--seed", type=int, default=0)
@@ -56,6 +114,9 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "config5_chain":
+        return run_chain(args)
 
     import numpy as np
     import torch
@@ -117,7 +178,14 @@ def main():
         step(i)
     prof = ctx.fkv_profile_read()
     ctx.fkv_profile_enable(False)
-    per_kernel_us = {name: 1e3 * ms / max(cnt, 1) for name, (ms, cnt) in prof.items()}
+    raw_us = {name: 1e3 * ms / max(cnt, 1) for name, (ms, cnt) in prof.items() if cnt}
+    # Each bracketed launch also pays for the event record in front of it.  The excess of the summed
+    # brackets over the un-profiled device time of the same step, spread over the launches, is that
+    # cost; it is removed so the figures are the kernels' own durations (they then agree with the
+    # rocprofv3 kernel trace).
+    launches_per_step = sum(cnt for _, cnt in prof.values()) / n_prof
+    event_cost_us = max(0.0, (sum(raw_us.values()) - dev_ms * 1e3) / max(launches_per_step, 1))
+    per_kernel_us = {name: max(v - event_cost_us, 0.0) for name, v in raw_us.items()}
     alg = kernel_algorithmic_bytes(L, k_tsp, budget)
     dominant = max(per_kernel_us, key=per_kernel_us.get)
     dom_gbs = alg[dominant] / (per_kernel_us[dominant] * 1e-6) / 1e9
@@ -168,7 +236,8 @@ def main():
         "path": {"algorithmic_bytes": total_bytes, "achieved_GBps": total_bytes / (wall_ms * 1e-3) / 1e9,
                  "frac_of_peak": total_bytes / (wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                  "device_ms_per_step": dev_ms, "warm_ms_per_step": warm_wall_ms, "warm_device_ms": warm_dev_ms,
-                 "per_kernel_us": per_kernel_us, "measured_copy_GBps": copy_gbs,
+                 "per_kernel_us": per_kernel_us, "event_record_cost_us": event_cost_us,
+                 "measured_copy_GBps": copy_gbs,
                  "frac_of_measured_copy": total_bytes / (wall_ms * 1e-3) / 1e9 / copy_gbs},
         "context": {"paper": "FastKV reports up to 1.82x prefill and 2.87x decode speedup on one NVIDIA A100 SXM "
                              "(LLaMA-3.1-8B-Instruct); its token-importance estimation costs 0.04 s per 32K prefill "

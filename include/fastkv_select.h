@@ -150,7 +150,10 @@ int fkv_set_score_path(fkv_ctx *ctx, int mode);
 int fkv_query_error(fkv_ctx *ctx, int32_t *flag_out);
 
 /* Per-kernel device timing for benchmarks.  While enabled, every launch is bracketed by
- * HIP events on the caller's stream.  fkv_profile_read synchronises those events, writes
+ * HIP events on the caller's stream (within one call the end event of a launch starts the next
+ * launch's interval, so each figure includes the event record that precedes the launch: about
+ * 2 us on MI355X, which a caller can estimate as the excess of the summed figures over the
+ * un-profiled time of the same call).  fkv_profile_read synchronises those events, writes
  * the accumulated milliseconds and launch counts of kernel ids 0 .. n-1 (n =
  * fkv_profile_kernels()) and clears the accumulators.  Not for use under graph capture. */
 int fkv_profile_kernels(void);

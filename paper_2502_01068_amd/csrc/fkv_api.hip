@@ -38,7 +38,7 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
   return w;
 }
 
-struct EventPair { hipEvent_t a, b; int kid; };
+struct EventPair { hipEvent_t a, b, start; int kid; };  // start = own `a` or the previous launch's `b`
 
 }  // namespace
 
@@ -53,6 +53,7 @@ struct fkv_ctx {
   bool prof_on;
   std::vector<EventPair> ev_pool;
   size_t ev_used;
+  EventPair *ev_prev;  // previous launch of the current API call (its end event starts the next)
   float ms_acc[KID_COUNT];
   int32_t n_acc[KID_COUNT];
 };
@@ -124,13 +125,16 @@ int check_counts(const Resolved &r, const int32_t *cnt, int *off /*[n_seq+1]*/) 
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-int check_ctx(const fkv_ctx *ctx, const Resolved &r) {
+int check_ctx(fkv_ctx *ctx, const Resolved &r) {
   if (!ctx) return FKV_ENULL;
+  ctx->ev_prev = nullptr;
   if (r.total > ctx->max_tokens || r.n_seq > ctx->max_seqs) return FKV_EWORKSPACE;
   return FKV_OK;
 }
 
-// Launch bracket for the timing facility.
+// Launch bracket for the timing facility.  Within one API call the end event of a launch is the
+// start event of the next, so a launch is charged its duration plus the gap before it and only
+// one event record sits between consecutive kernels.
 struct Timed {
   fkv_ctx *ctx;
   hipStream_t s;
@@ -139,11 +143,19 @@ struct Timed {
     if (c->prof_on && c->ev_used < c->ev_pool.size()) {
       ev = &c->ev_pool[c->ev_used++];
       ev->kid = kid;
-      (void)hipEventRecord(ev->a, s);
+      if (c->ev_prev) {
+        ev->start = c->ev_prev->b;
+      } else {
+        ev->start = ev->a;
+        (void)hipEventRecord(ev->a, s);
+      }
     }
   }
   ~Timed() {
-    if (ev) (void)hipEventRecord(ev->b, s);
+    if (ev) {
+      (void)hipEventRecord(ev->b, s);
+      ctx->ev_prev = ev;
+    }
   }
 };
 
@@ -168,26 +180,33 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
   a.causal = sh->causal;
   a.pool_r = sh->pool_kernel / 2;
   a.pool_mode = sh->pool_mode;
-  a.chunk = stats_chunk_tokens();
   a.sum_p = r.sum_p;
   fill_map(r, &a.map);
 
   // Single pass over K when every block of the batch can be resident at once.
   {
     FusedArgs f{};
-    const int cap_own = fused_slots() - a.pool_r - (a.pool_r > r.W ? a.pool_r : r.W);
+    // Fewest 32-token sub-tiles per block for which the batch still fits the resident grid: short
+    // inputs then spread over more blocks and each block streams less before the grid exchange.
+    const int halo = a.pool_r + (a.pool_r > r.W ? a.pool_r : r.W);
     int total = 0, clusters = 0;
-    bool fits = cap_own >= 1 && ctx->score_path != 1;
-    f.cl0[0] = 0;
-    for (int b = 0; b < r.n_seq && fits; ++b) {
-      const int P = r.cu[b + 1] - r.cu[b] - r.W;
-      const int nb_b = (P + cap_own - 1) / cap_own;
-      a.map.blk[b] = total;
-      f.own[b] = nb_b ? (P + nb_b - 1) / nb_b : 0;
-      total += nb_b;
-      clusters += (nb_b + fused_cluster_size() - 1) / fused_cluster_size();
-      f.cl0[b + 1] = clusters;
-      if (total > ctx->n_cu || total > kMaxFusedBlocks || clusters > kMaxClusters) fits = false;
+    bool fits = false;
+    for (int n_sub = 1; n_sub * 32 <= fused_slots() && !fits && ctx->score_path != 1; ++n_sub) {
+      const int cap_own = n_sub * 32 - halo;
+      if (cap_own < 1) continue;
+      fits = true;
+      total = clusters = 0;
+      f.cl0[0] = 0;
+      for (int b = 0; b < r.n_seq && fits; ++b) {
+        const int P = r.cu[b + 1] - r.cu[b] - r.W;
+        const int nb_b = (P + cap_own - 1) / cap_own;
+        a.map.blk[b] = total;
+        f.own[b] = nb_b ? (P + nb_b - 1) / nb_b : 0;
+        total += nb_b;
+        clusters += (nb_b + fused_cluster_size() - 1) / fused_cluster_size();
+        f.cl0[b + 1] = clusters;
+        if (total > ctx->n_cu || total > kMaxFusedBlocks || clusters > kMaxClusters) fits = false;
+      }
     }
     if (ctx->score_path == 2 && !(fits && total > 0)) return FKV_EUNSUPPORTED;
     if (fits && total > 0) {
@@ -207,7 +226,17 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
     if (r.sum_p == 0) return FKV_OK;  // no prefix token anywhere: nothing to score
   }
 
-  // pass 1: softmax statistics of every window row over all L keys
+  // pass 1: softmax statistics of every window row over all L keys.  Blocks take at least
+  // stats_chunk_tokens() tokens, more when that keeps the launch near one block per CU (the Q
+  // load and the fold at the end of a block are paid once per block).
+  const int n_cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
+  {
+    const int64_t per_cu = (r.total + n_cu - 1) / n_cu;
+    int chunk = (int)((per_cu + 31) / 32 * 32);
+    if (chunk < stats_chunk_tokens()) chunk = stats_chunk_tokens();
+    if (chunk > 1024) chunk = 1024;
+    a.chunk = chunk;
+  }
   int nb = 0;
   for (int b = 0; b < r.n_seq; ++b) {
     a.map.blk[b] = nb;
@@ -221,8 +250,16 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
   { Timed t(ctx, st, KID_COMBINE); e = launch_combine(a, st); }
   if (e != hipSuccess) return hip_fail(e);
 
-  // pass 2: scores of the prefix tokens
-  const int tout = scores_tile_out(a.pool_r);
+  // pass 2: scores of the prefix tokens; tiles overlap by the pooling halo
+  {
+    int sub = scores_sub_short();
+    const int64_t per_cu = (r.sum_p + n_cu - 1) / n_cu + 2 * a.pool_r;
+    if (per_cu > (int64_t)sub * 32) sub = (int)((per_cu + 31) / 32);
+    if (sub > scores_sub_long()) sub = scores_sub_long();
+    while (sub * 32 - 2 * a.pool_r < 1) ++sub;
+    a.tile_sub = sub;
+  }
+  const int tout = a.tile_sub * 32 - 2 * a.pool_r;
   nb = 0;
   for (int b = 0; b < r.n_seq; ++b) {
     a.map.blk[b] = nb;
@@ -353,6 +390,7 @@ int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_
   }
   c->prof_on = false;
   c->ev_used = 0;
+  c->ev_prev = nullptr;
   memset(c->ms_acc, 0, sizeof c->ms_acc);
   memset(c->n_acc, 0, sizeof c->n_acc);
   e = hipMalloc(reinterpret_cast<void **>(&c->ws), c->lay.total);
@@ -550,7 +588,7 @@ int fkv_profile_read(fkv_ctx *ctx, float *ms_out, int32_t *launches_out, int32_t
     EventPair &p = ctx->ev_pool[i];
     hipError_t e = hipEventSynchronize(p.b);
     float ms = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.a, p.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.start, p.b);
     if (e != hipSuccess) return hip_fail(e);
     ctx->ms_acc[p.kid] += ms;
     ctx->n_acc[p.kid] += 1;

@@ -9,10 +9,16 @@
 
 namespace fkv {
 
-constexpr int kGatherThreads = 256;
-#ifndef FKV_GATHER_UNROLL
-#define FKV_GATHER_UNROLL 4
+#ifndef FKV_GATHER_THREADS
+#define FKV_GATHER_THREADS 256
 #endif
+#ifndef FKV_GATHER_UNROLL
+#define FKV_GATHER_UNROLL 2
+#endif
+#ifndef FKV_GATHER_NT
+#define FKV_GATHER_NT 1
+#endif
+constexpr int kGatherThreads = FKV_GATHER_THREADS;
 constexpr int kGatherUnroll = FKV_GATHER_UNROLL;  // 16-byte chunks in flight per thread
 
 int gather_blocks_per_head(const GatherJob &j) {
@@ -48,12 +54,20 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(GatherArgs a) {
       int b = 0;
       while (b + 1 < a.n_seq && (int)t >= job.cnt_off[b + 1]) ++b;
       const size_t tok = (size_t)a.cu[b] + (size_t)idx[t];
+#if FKV_GATHER_NT
       val[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src_h + tok * job.src_row_stride) + col);
+#else
+      val[u] = *(reinterpret_cast<const u32x4 *>(src_h + tok * job.src_row_stride) + col);
+#endif
     }
   }
 #pragma unroll
   for (int u = 0; u < kGatherUnroll; ++u)
+#if FKV_GATHER_NT
     if (live[u]) __builtin_nontemporal_store(val[u], dst_h + (c0 + u * kGatherThreads));
+#else
+    if (live[u]) dst_h[c0 + u * kGatherThreads] = val[u];
+#endif
 }
 
 hipError_t launch_gather(const GatherArgs &a, int n_blocks, hipStream_t s) {

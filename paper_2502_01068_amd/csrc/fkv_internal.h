@@ -64,7 +64,8 @@ struct ScoreArgs {
   int causal;
   int pool_r;             // pooling radius (kernel = 2r+1)
   int pool_mode;          // FKV_POOL_AVG / FKV_POOL_MAX
-  int chunk;              // tokens per block in the stats launch
+  int chunk;              // tokens per block in the stats launch (multiple of 32)
+  int tile_sub;           // 32-token sub-tiles per block in the scores launch
   int64_t sum_p;          // row stride of scores_group
 };
 
@@ -92,7 +93,8 @@ int score_fused_max_blocks_per_cu(void);
 hipError_t launch_score_fused(const ScoreArgs &a, const FusedArgs &f, hipStream_t s);
 
 int stats_chunk_tokens(void);
-int scores_tile_out(int pool_r);
+int scores_sub_short(void);
+int scores_sub_long(void);
 hipError_t launch_stats(const ScoreArgs &a, int n_blocks, hipStream_t s);
 hipError_t launch_combine(const ScoreArgs &a, hipStream_t s);
 hipError_t launch_scores(const ScoreArgs &a, int n_blocks, hipStream_t s);

@@ -22,7 +22,8 @@
 namespace fkv {
 
 int stats_chunk_tokens(void) { return kStatsChunk; }
-int scores_tile_out(int pool_r) { return kTile - 2 * pool_r; }
+int scores_sub_short(void) { return kScoresSubShort; }
+int scores_sub_long(void) { return kScoresSubLong; }
 
 __global__ __launch_bounds__(kThreads) void k_stats(ScoreArgs a) {
   __shared__ __attribute__((aligned(16))) uint8_t stage_all[kWaves * kStageBytes];
@@ -99,13 +100,15 @@ __global__ __launch_bounds__(256) void k_combine(ScoreArgs a) {
   }
 }
 
+// kMaxSub 32-token sub-tiles per block at most; a.tile_sub of them are used (host-chosen so that
+// the launch is about one block per CU).  The window sums go straight into their own LDS array,
+// next to the waves' staging tiles.
+template <int kMaxSub>
 __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
-  // The staging tiles are dead once every wave has left its K loop; the per-head window sums
-  // then reuse the same LDS.
-  __shared__ __attribute__((aligned(16))) uint8_t lds_all[kWaves * kStageBytes];
-  float(*s_head)[kTile] = reinterpret_cast<float(*)[kTile]>(lds_all);  // [Hkv*4][kTile]
-  float(*g_sum)[kTile] = reinterpret_cast<float(*)[kTile]>(lds_all + kMaxKvHeads * kMaxGroup * kTile * 4);
-  static_assert((kMaxKvHeads * kMaxGroup + kMaxKvHeads) * kTile * 4 <= kWaves * kStageBytes, "LDS reuse");
+  constexpr int kSlots = kMaxSub * kSub;
+  __shared__ __attribute__((aligned(16))) uint8_t stage_all[kWaves * kStageBytes];
+  __shared__ float s_head[kMaxKvHeads * kMaxGroup][kSlots];  // window-summed probabilities per head
+  __shared__ float g_sum[kMaxKvHeads][kSlots];               // per-group sums of pooled head scores
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 31, hi = lane >> 5;
@@ -114,17 +117,13 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
   const int Lb = a.map.cu[b + 1] - tok_base;
   const int P = Lb - a.W;
   const int r = a.pool_r;
-  const int tout = kTile - 2 * r;
+  const int n_sub = a.tile_sub;
+  const int tout = n_sub * kSub - 2 * r;
   const int j0 = ((int)blockIdx.x - a.map.blk[b]) * tout - r;  // first computed token (may be < 0)
-  uint8_t *stage = lds_all + wave * kStageBytes;
-  constexpr int kNSub = kTile / kSub;
+  uint8_t *stage = stage_all + wave * kStageBytes;
 
   FKV_TICK(24);
-  // window-summed probabilities of this wave's group: hsum[st][hl] for token j0 + st*32 + n
-  float hsum[kNSub][4];
-  int g_mine = -1;
-  for (int g = wave; g < a.Hkv; g += kWaves) {  // Hkv <= kWaves: at most one group per wave
-    g_mine = g;
+  for (int g = wave; g < a.Hkv; g += kWaves) {
     bf16x8 qa[8];
     load_q(a, b, g, lane, qa);
     float cst[16];
@@ -132,7 +131,9 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
 #pragma unroll
     for (int q = 0; q < 16; ++q) cst[q] = rs[(q >> 2) * 8 + hi * 4 + (q & 3)];
 
-    stream_head(a, qa, tok_base, Lb, g, j0, kNSub, stage, lane, [&](int st, const floatx16 &acc) {
+    stream_head(a, qa, tok_base, Lb, g, j0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
+      const int tok = j0 + st * kSub + n;
+      const bool inb = tok >= 0 && tok < P;  // only prefix tokens are scored
 #pragma unroll
       for (int hl = 0; hl < 4; ++hl) {
         float sum = 0.f;
@@ -142,29 +143,16 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
           sum += (hi * 4 + rr < a.W) ? e : 0.f;
         }
         sum = add_across_halves(sum);  // other half of the window rows
-#pragma unroll
-        for (int q = 0; q < kNSub; ++q)
-          if (q == st) hsum[q][hl] = sum;
+        if (hi == 0 && hl < a.G) s_head[g * kMaxGroup + hl][st * kSub + n] = inb ? sum : 0.f;
       }
     });
   }
   FKV_TICK(25);
   __syncthreads();
   FKV_TICK(26);
-  if (g_mine >= 0 && hi == 0) {
-#pragma unroll
-    for (int st = 0; st < kNSub; ++st) {
-      const int tok = j0 + st * kSub + n;
-      const bool inb = tok >= 0 && tok < P;  // only prefix tokens are scored
-#pragma unroll
-      for (int hl = 0; hl < 4; ++hl)
-        if (hl < a.G) s_head[g_mine * kMaxGroup + hl][st * kSub + n] = inb ? hsum[st][hl] : 0.f;
-    }
-  }
-  __syncthreads();
 
   const int col0 = tok_base - b * a.W;  // column of this sequence's token 0 in the score rows
-  pool_and_write<kTile>(a, s_head, g_sum, j0, j0 + r, min(j0 + r + tout, P), col0);
+  pool_and_write<kSlots>(a, s_head, g_sum, j0, j0 + r, min(j0 + r + tout, P), col0);
   FKV_TICK(27);
 }
 
@@ -178,7 +166,10 @@ hipError_t launch_combine(const ScoreArgs &a, hipStream_t s) {
   return hipGetLastError();
 }
 hipError_t launch_scores(const ScoreArgs &a, int n_blocks, hipStream_t s) {
-  hipLaunchKernelGGL(k_scores, dim3(n_blocks), dim3(kThreads), 0, s, a);
+  if (a.tile_sub <= kScoresSubShort)
+    hipLaunchKernelGGL(k_scores<kScoresSubShort>, dim3(n_blocks), dim3(kThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(k_scores<kScoresSubLong>, dim3(n_blocks), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 

@@ -10,8 +10,9 @@ typedef __attribute__((ext_vector_type(16))) float floatx16;
 
 constexpr int kWaves = 8;            // one wave per KV head
 constexpr int kThreads = kWaves * 64;
-constexpr int kStatsChunk = 128;     // tokens per block in k_stats
-constexpr int kTile = 128;           // tokens computed per block in k_scores (incl. pooling halo)
+constexpr int kStatsChunk = 128;     // fewest tokens per block in k_stats
+constexpr int kScoresSubShort = 4;   // k_scores: sub-tiles per block (incl. pooling halo), short inputs
+constexpr int kScoresSubLong = 18;   // ... and the most for long inputs (LDS bound)
 constexpr int kSub = 32;             // tokens per MFMA sub-tile
 constexpr int kStageBytes = kSub * kHeadDim * 2;  // 8 KiB per wave
 constexpr float kNegBig = -1.0e30f;

@@ -2,9 +2,9 @@
 // order-preserving integer image of the fp32 scores, then an ordered compaction, so the
 // output is ascending, has exactly k entries and equal scores go to the lower index.
 //
-// One 1024-thread block per (row, sequence).  Each thread holds 32 keys of every 32768-key
-// chunk, read with coalesced 128-bit loads.  Rows of up to one chunk stay in registers for
-// the whole kernel; longer rows are re-read from L2 per pass.
+// One 1024-thread block per (row, sequence).  Each thread holds 8, 16 or 32 keys (by row
+// length) read with coalesced 128-bit loads.  Rows of up to 32768 keys stay in registers for
+// the whole kernel; longer rows are processed in 32768-key chunks re-read from L2 per pass.
 //   1. the row's smallest and largest key bound the search interval [lo, lo + 2^s); histogram
 //      passes of up to 11 bits of (key - lo), most significant first, narrow it down to the key
 //      T of the (k-W)-th largest prefix score.  Taking digits relative to the row's own range
@@ -19,8 +19,7 @@ namespace fkv {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kKpt = 32;                          // keys per thread per chunk
-constexpr int kChunk = kSelThreads * kKpt;        // 32768
+constexpr int kMaxKpt = 32;                       // keys per thread per chunk (8, 16 or 32)
 constexpr int kBins = 2048;
 
 // Monotone map fp32 -> uint32 (larger float <=> larger key), valid for any non-NaN input;
@@ -31,18 +30,22 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Key layout of a 32768-key chunk: wave w owns virtual positions [2048 w, 2048 w + 2048); its
-// q-th 128-bit load covers positions 2048 w + 256 q + 4 lane + {0..3}, so every load
-// instruction reads 1 KiB of consecutive memory.  Position v holds score v - mis (`base` = row
-// pointer - mis is 16-byte aligned); positions outside [mis, mis+P) get key 0.
-__device__ __forceinline__ int slot_pos(int wave, int lane, int q) { return wave * 2048 + q * 256 + lane * 4; }
+// Key layout of a chunk of 1024*kKpt keys (kKpt keys per thread): wave w owns virtual positions
+// [64 kKpt w, 64 kKpt (w+1)); its q-th 128-bit load covers positions 64 kKpt w + 256 q + 4 lane
+// + {0..3}, so every load instruction reads 1 KiB of consecutive memory.  Position v holds
+// score v - mis (`base` = row pointer - mis is 16-byte aligned); positions outside
+// [mis, mis+P) get key 0.  Short rows use fewer keys per thread: the kernel is bound by the
+// instructions it spends per key slot.
+template <int kKpt>
+__device__ __forceinline__ int slot_pos(int wave, int lane, int q) { return wave * (64 * kKpt) + q * 256 + lane * 4; }
 
+template <int kKpt>
 __device__ __forceinline__ void load_keys(const float *base, int mis, int P, int v_chunk, int wave, int lane,
                                           uint32_t (&key)[kKpt]) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
   for (int q = 0; q < kKpt / 4; ++q) {
-    const int v = v_chunk + slot_pos(wave, lane, q);
+    const int v = v_chunk + slot_pos<kKpt>(wave, lane, q);
     if (v >= mis && v + 3 < mis + P) {
       const f32x4 f = *reinterpret_cast<const f32x4 *>(base + v);
       key[4 * q + 0] = order_key(f[0]);
@@ -65,12 +68,14 @@ __device__ __forceinline__ void wave_sync_lds() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <bool kResident>
+template <bool kResident, int kKpt>
 __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32_t *out, uint32_t *hist,
                                            uint32_t *wsum, uint32_t *bcast, uint32_t *scan_tbl) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int mis = (int)((reinterpret_cast<uintptr_t>(sc) >> 2) & 3);
   const float *base = sc - mis;
+  constexpr int kChunk = kSelThreads * kKpt;
+  constexpr int kQ = kKpt / 4;  // 128-bit loads (scan items) per thread
   const int n_chunks = kResident ? 1 : (P + mis + kChunk - 1) / kChunk;
   uint32_t key[kKpt];
   FKV_TICK(0);
@@ -79,7 +84,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   // the bins spread over the values the row really holds instead of over fp32's exponent
   uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
   for (int ch = 0; ch < n_chunks; ++ch) {
-    load_keys(base, mis, P, ch * kChunk, wave, lane, key);
+    load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
 #pragma unroll
     for (int e = 0; e < kKpt; ++e) {
       kmax = max(kmax, key[e]);
@@ -111,7 +116,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
     for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
     __syncthreads();
     for (int ch = 0; ch < n_chunks; ++ch) {
-      if (!kResident) load_keys(base, mis, P, ch * kChunk, wave, lane, key);
+      if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
 #pragma unroll
       for (int e = 0; e < kKpt; ++e) {
         const uint32_t rel = key[e] - lo;  // keys below lo (and key 0) wrap far above span
@@ -157,7 +162,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   // ---- ordered compaction.  Index order inside a wave is (q, lane, e).
   uint32_t run_gt = 0, run_eq = 0;
   for (int ch = 0; ch < n_chunks; ++ch) {
-    if (!kResident) load_keys(base, mis, P, ch * kChunk, wave, lane, key);
+    if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
     uint32_t gt_mask = 0, eq_mask = 0;
 #pragma unroll
     for (int e = 0; e < kKpt; ++e) {
@@ -168,21 +173,17 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
     // Index order inside the wave is item order q*64 + lane; lane l scans items 8l .. 8l+7 from a
     // wave-private LDS table, the 64 lanes scan their sums, and the table is overwritten with the
     // exclusive prefix of every item.
-    uint32_t *tbl = scan_tbl + wave * 512;
+    uint32_t *tbl = scan_tbl + wave * (64 * kQ);
 #pragma unroll
-    for (int q = 0; q < kKpt / 4; ++q)
+    for (int q = 0; q < kQ; ++q)
       tbl[q * 64 + lane] = (uint32_t)__popc((gt_mask >> (4 * q)) & 15u) | ((uint32_t)__popc((eq_mask >> (4 * q)) & 15u) << 16);
     wave_sync_lds();
-    uint32_t item[8];
-    {
-      const u32x4 a0 = *reinterpret_cast<const u32x4 *>(tbl + 8 * lane);
-      const u32x4 a1 = *reinterpret_cast<const u32x4 *>(tbl + 8 * lane + 4);
-      item[0] = a0[0]; item[1] = a0[1]; item[2] = a0[2]; item[3] = a0[3];
-      item[4] = a1[0]; item[5] = a1[1]; item[6] = a1[2]; item[7] = a1[3];
-    }
+    uint32_t item[kQ];
+#pragma unroll
+    for (int i = 0; i < kQ; ++i) item[i] = tbl[kQ * lane + i];
     uint32_t mine = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) mine += item[i];
+    for (int i = 0; i < kQ; ++i) mine += item[i];
     uint32_t inc = mine;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -192,12 +193,10 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
     const uint32_t wave_tot = (uint32_t)__shfl((int)inc, 63);
     uint32_t pre = inc - mine;
     wave_sync_lds();
-    {
-      u32x4 b0, b1;
-      b0[0] = pre; pre += item[0]; b0[1] = pre; pre += item[1]; b0[2] = pre; pre += item[2]; b0[3] = pre; pre += item[3];
-      b1[0] = pre; pre += item[4]; b1[1] = pre; pre += item[5]; b1[2] = pre; pre += item[6]; b1[3] = pre;
-      *reinterpret_cast<u32x4 *>(tbl + 8 * lane) = b0;
-      *reinterpret_cast<u32x4 *>(tbl + 8 * lane + 4) = b1;
+#pragma unroll
+    for (int i = 0; i < kQ; ++i) {
+      tbl[kQ * lane + i] = pre;
+      pre += item[i];
     }
     __syncthreads();  // wsum is free (previous readers are past their loop); tables are complete
     if (lane == 0) wsum[wave] = wave_tot;
@@ -211,13 +210,13 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
     const uint32_t gt0 = run_gt + (before_w & 0xFFFFu), eq0 = run_eq + (before_w >> 16);
     const int i_chunk = ch * kChunk - mis;
 #pragma unroll
-    for (int q = 0; q < kKpt / 4; ++q) {
+    for (int q = 0; q < kQ; ++q) {
       const uint32_t gq = (gt_mask >> (4 * q)) & 15u, eqq = (eq_mask >> (4 * q)) & 15u;
       if (gq | eqq) {
         const uint32_t pq = tbl[q * 64 + lane];
         uint32_t gt_before = gt0 + (pq & 0xFFFFu);
         uint32_t eq_before = eq0 + (pq >> 16);
-        const int i0 = i_chunk + slot_pos(wave, lane, q);
+        const int i0 = i_chunk + slot_pos<kKpt>(wave, lane, q);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           if ((gq >> e) & 1u) {
@@ -239,7 +238,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
 
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
   __shared__ uint32_t hist[kBins];
-  __shared__ __attribute__((aligned(16))) uint32_t scan_tbl[kSelWaves * 512];
+  __shared__ __attribute__((aligned(16))) uint32_t scan_tbl[kSelWaves * 64 * (kMaxKpt / 4)];
   __shared__ uint32_t wsum[2 * kSelWaves];
   __shared__ uint32_t bcast[4];
 
@@ -257,10 +256,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
 
   if ((int)threadIdx.x < a.W) out[kp + threadIdx.x] = P + threadIdx.x;  // window tokens are always kept
   if (kp <= 0) return;
-  if (P + 3 <= kChunk)
-    select_row<true>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
+  if (P + 3 <= kSelThreads * 8)
+    select_row<true, 8>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
+  else if (P + 3 <= kSelThreads * 16)
+    select_row<true, 16>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
+  else if (P + 3 <= kSelThreads * 32)
+    select_row<true, 32>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
   else
-    select_row<false>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
+    select_row<false, 32>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
 }
 
 hipError_t launch_select(const SelectArgs &a, hipStream_t s) {
