@@ -9,7 +9,9 @@
 //      passes of up to 11 bits of (key - lo), most significant first, narrow it down to the key
 //      T of the (k-W)-th largest prefix score.  Taking digits relative to the row's own range
 //      spreads the keys over the 2048 LDS bins (fp32 exponents would crowd them into a few
-//      dozen) and makes a constant row cost no pass at all;
+//      dozen) and makes a constant row cost no pass at all.  After the first pass the few keys
+//      left in the interval are collected into LDS, one per thread, and the remaining passes
+//      run on that list;
 //   2. a scan of the per-item keep counts (in-wave through an LDS table, across waves through
 //      wave totals) gives every kept key its output offset in index order: all keys > T and
 //      the first `need_eq` keys == T by index.
@@ -108,23 +110,11 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   // ---- narrow [lo, lo + 2^s) down to the key T of the kp-th largest score
   uint32_t lo = kmin, remaining = (uint32_t)kp, need_eq = remaining;
   int s = (kmax == kmin) ? 0 : 32 - __clz(kmax - kmin);  // kmax - kmin < 2^s
-  while (s > 0) {
-    const int bits = min(11, s);
-    const int shift = s - bits;
-    const uint32_t span = (s >= 32) ? 0xFFFFFFFFu : ((1u << s) - 1u);  // candidates: key - lo <= span
-    __syncthreads();  // wsum / hist / bcast readers of the previous round are done
-    for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
-    __syncthreads();
-    for (int ch = 0; ch < n_chunks; ++ch) {
-      if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
-#pragma unroll
-      for (int e = 0; e < kKpt; ++e) {
-        const uint32_t rel = key[e] - lo;  // keys below lo (and key 0) wrap far above span
-        if (key[e] >= lo && rel <= span) atomicAdd(&hist[rel >> shift], 1u);
-      }
-    }
-    __syncthreads();
-    FKV_TICK(8 + 2 * (s > 22 ? 0 : (s > 11 ? 1 : 2)));
+  bool whole_bin = false;
+
+  // Picks the histogram bin that holds the `remaining`-th largest candidate and narrows the
+  // interval to it.  Expects hist filled and a barrier passed; leaves a barrier behind.
+  auto narrow = [&](int shift) {
     // thread owns bins 2*tid, 2*tid+1; suffix sums from the top bin down
     const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
     const uint32_t mine = h0 + h1;
@@ -146,14 +136,93 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
       bcast[0] = lo + (digit << shift);
       bcast[1] = rem;
       bcast[2] = (in_bin == rem) ? 1u : 0u;  // the whole bin is kept: no need to refine further
+      bcast[3] = in_bin;
     }
     __syncthreads();
     lo = bcast[0];
     remaining = bcast[1];
     need_eq = remaining;
     s = shift;
-    if (bcast[2]) { need_eq = 0xFFFFFFFFu; break; }
+    whole_bin = bcast[2] != 0u;
+    return bcast[3];  // candidates left
+  };
+  auto clear_hist = [&]() {
+    __syncthreads();  // wsum / hist / bcast readers of the previous round are done
+    for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
+    if (tid == 0) bcast[4] = 0;  // candidate-list length
+    __syncthreads();
+  };
+
+  uint32_t n_cand = 0xFFFFFFFFu;
+  if (s > 0) {
+    // round 1: every key of the row
+    const int shift = s - min(11, s);
+    clear_hist();
+    for (int ch = 0; ch < n_chunks; ++ch) {
+      if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
+#pragma unroll
+      for (int e = 0; e < kKpt; ++e)  // branch-free: empty slots (key 0) count into the spare bin
+        atomicAdd(&hist[key[e] ? (key[e] - lo) >> shift : (uint32_t)kBins], 1u);
+    }
+    __syncthreads();
+    FKV_TICK(8);
+    n_cand = narrow(shift);
+    FKV_TICK(9);
   }
+  if (s > 0 && !whole_bin && n_cand <= (uint32_t)kSelThreads) {
+    // Few keys are left in the interval (typically ~1 %): collect them into LDS, one per thread, and
+    // finish the search on that list instead of sweeping all register keys again.
+    uint32_t *cand = scan_tbl;  // free until the compaction
+    const uint32_t span = (1u << s) - 1u;  // s <= 21 here
+    for (int ch = 0; ch < n_chunks; ++ch) {
+      if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
+#pragma unroll
+      for (int q = 0; q < kQ; ++q) {
+        // Valid keys lie in [0x007FFFFF, 0xFF800000] and span < 2^21, so a key below lo (or an
+        // empty slot) wraps above span: one unsigned compare per key, one branch per item.
+        const uint32_t r0 = key[4 * q] - lo, r1 = key[4 * q + 1] - lo, r2 = key[4 * q + 2] - lo, r3 = key[4 * q + 3] - lo;
+        if (min(min(r0, r1), min(r2, r3)) <= span) {
+          if (r0 <= span) cand[atomicAdd(&bcast[4], 1u)] = r0;
+          if (r1 <= span) cand[atomicAdd(&bcast[4], 1u)] = r1;
+          if (r2 <= span) cand[atomicAdd(&bcast[4], 1u)] = r2;
+          if (r3 <= span) cand[atomicAdd(&bcast[4], 1u)] = r3;
+        }
+      }
+    }
+    __syncthreads();
+    FKV_TICK(10);
+    const uint32_t my_rel = (uint32_t)tid < n_cand ? cand[tid] : 0xFFFFFFFFu;
+    uint32_t base_rel = 0;  // lo advanced since the list was built
+    while (s > 0 && !whole_bin) {
+      const int shift = s - min(11, s);
+      const uint32_t span2 = (1u << s) - 1u;
+      clear_hist();
+      const uint32_t rel = my_rel - base_rel;
+      if (my_rel >= base_rel && rel <= span2) atomicAdd(&hist[rel >> shift], 1u);
+      __syncthreads();
+      const uint32_t lo_before = lo;
+      narrow(shift);
+      base_rel += lo - lo_before;
+    }
+  } else {
+    while (s > 0 && !whole_bin) {
+      const int shift = s - min(11, s);
+      const uint32_t span = (s >= 32) ? 0xFFFFFFFFu : ((1u << s) - 1u);  // candidates: key - lo <= span
+      clear_hist();
+      for (int ch = 0; ch < n_chunks; ++ch) {
+        if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
+#pragma unroll
+        for (int e = 0; e < kKpt; ++e) {
+          const uint32_t rel = key[e] - lo;
+          if (key[e] >= lo && rel <= span) atomicAdd(&hist[rel >> shift], 1u);
+        }
+      }
+      __syncthreads();
+      narrow(shift);
+    }
+  }
+  if (whole_bin) need_eq = 0xFFFFFFFFu;
+  __syncthreads();  // the candidate list (scan table) is free again
   // keep key > T, and key == T while fewer than need_eq equal keys came before it.  When a whole
   // bin is kept, T is the smallest key the bin could hold and every key == T is kept.
   const uint32_t T = lo;
@@ -163,20 +232,22 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   uint32_t run_gt = 0, run_eq = 0;
   for (int ch = 0; ch < n_chunks; ++ch) {
     if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
-    uint32_t gt_mask = 0, eq_mask = 0;
+    uint32_t cnt[kQ];   // per 4-key item: keys > T (low 16 bits), keys == T (high 16 bits)
 #pragma unroll
-    for (int e = 0; e < kKpt; ++e) {
-      gt_mask |= (key[e] > T) ? (1u << e) : 0u;
-      eq_mask |= (key[e] == T) ? (1u << e) : 0u;
+    for (int q = 0; q < kQ; ++q) {
+      uint32_t c = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) c += (key[4 * q + e] > T ? 1u : 0u) + (key[4 * q + e] == T ? 0x10000u : 0u);
+      cnt[q] = c;
     }
     // Kept counts per (q, lane) item, packed (low 16 bits: keys > T, high 16 bits: keys == T).
     // Index order inside the wave is item order q*64 + lane; lane l scans items 8l .. 8l+7 from a
     // wave-private LDS table, the 64 lanes scan their sums, and the table is overwritten with the
     // exclusive prefix of every item.
-    uint32_t *tbl = scan_tbl + wave * (64 * kQ);
+    FKV_TICK(4);
+    uint32_t *tbl = scan_tbl + wave * (64 * kMaxKpt);  // 64*kQ table entries, then up to 64*kKpt staged outputs
 #pragma unroll
-    for (int q = 0; q < kQ; ++q)
-      tbl[q * 64 + lane] = (uint32_t)__popc((gt_mask >> (4 * q)) & 15u) | ((uint32_t)__popc((eq_mask >> (4 * q)) & 15u) << 16);
+    for (int q = 0; q < kQ; ++q) tbl[q * 64 + lane] = cnt[q];
     wave_sync_lds();
     uint32_t item[kQ];
 #pragma unroll
@@ -198,6 +269,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
       tbl[kQ * lane + i] = pre;
       pre += item[i];
     }
+    FKV_TICK(5);
     __syncthreads();  // wsum is free (previous readers are past their loop); tables are complete
     if (lane == 0) wsum[wave] = wave_tot;
     __syncthreads();
@@ -207,28 +279,49 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
       if (w < wave) before_w += v;
       total += v;
     }
+    FKV_TICK(6);
+    // Kept indices are first placed in the wave's LDS region (its outputs are consecutive in the
+    // result because index order is kept), then written out with full 64-lane stores.
+    uint32_t pq[kQ];
+#pragma unroll
+    for (int q = 0; q < kQ; ++q) pq[q] = tbl[q * 64 + lane];
+    wave_sync_lds();  // every lane holds its prefixes: the region can be reused for staging
     const uint32_t gt0 = run_gt + (before_w & 0xFFFFu), eq0 = run_eq + (before_w >> 16);
+    const uint32_t wave_base = gt0 + min(eq0, need_eq);
+    const uint32_t wave_end = gt0 + (wave_tot & 0xFFFFu) + min(eq0 + (wave_tot >> 16), need_eq);
+    int32_t *stg = reinterpret_cast<int32_t *>(tbl);
+    int32_t *dummy = reinterpret_cast<int32_t *>(bcast) + 8 + lane;  // sink for keys that are dropped
     const int i_chunk = ch * kChunk - mis;
 #pragma unroll
     for (int q = 0; q < kQ; ++q) {
-      const uint32_t gq = (gt_mask >> (4 * q)) & 15u, eqq = (eq_mask >> (4 * q)) & 15u;
-      if (gq | eqq) {
-        const uint32_t pq = tbl[q * 64 + lane];
-        uint32_t gt_before = gt0 + (pq & 0xFFFFu);
-        uint32_t eq_before = eq0 + (pq >> 16);
-        const int i0 = i_chunk + slot_pos<kKpt>(wave, lane, q);
+      uint32_t gt_before = gt0 + (pq[q] & 0xFFFFu);
+      uint32_t eq_before = eq0 + (pq[q] >> 16);
+      const int i0 = i_chunk + slot_pos<kKpt>(wave, lane, q);
+      if ((cnt[q] >> 16) == 0) {
+        // no key of this item ties with T: branch-free placement
+        int32_t *dst = stg + (gt_before + min(eq_before, need_eq) - wave_base);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          if ((gq >> e) & 1u) {
-            out[gt_before + min(eq_before, need_eq)] = i0 + e;
+          const bool kept = key[4 * q + e] > T;
+          *(kept ? dst : dummy) = i0 + e;
+          dst += kept ? 1 : 0;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t kk = key[4 * q + e];
+          if (kk > T) {
+            stg[gt_before + min(eq_before, need_eq) - wave_base] = i0 + e;
             ++gt_before;
-          } else if ((eqq >> e) & 1u) {
-            if (eq_before < need_eq) out[gt_before + eq_before] = i0 + e;
+          } else if (kk == T) {
+            if (eq_before < need_eq) stg[gt_before + eq_before - wave_base] = i0 + e;
             ++eq_before;
           }
         }
       }
     }
+    wave_sync_lds();
+    for (uint32_t o = lane; o < wave_end - wave_base; o += 64) out[wave_base + o] = stg[o];
     __syncthreads();  // the tables are rewritten by the next chunk
     run_gt += total & 0xFFFFu;
     run_eq += total >> 16;
@@ -237,10 +330,10 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
-  __shared__ uint32_t hist[kBins];
-  __shared__ __attribute__((aligned(16))) uint32_t scan_tbl[kSelWaves * 64 * (kMaxKpt / 4)];
+  __shared__ uint32_t hist[kBins + 1];  // + spare bin for empty key slots
+  __shared__ __attribute__((aligned(16))) uint32_t scan_tbl[kSelWaves * 64 * kMaxKpt];  // 128 KiB: scan tables / output staging
   __shared__ uint32_t wsum[2 * kSelWaves];
-  __shared__ uint32_t bcast[4];
+  __shared__ uint32_t bcast[8 + 64];  // broadcast slots, then one sink word per lane
 
   int row = blockIdx.x;
   const int set_id = (a.n_sets > 1 && row >= a.set[0].n_rows) ? 1 : 0;
