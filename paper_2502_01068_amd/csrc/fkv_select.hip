@@ -15,60 +15,9 @@
 //   2. a scan of the per-item keep counts (in-wave through an LDS table, across waves through
 //      wave totals) gives every kept key its output offset in index order: all keys > T and
 //      the first `need_eq` keys == T by index.
-#include "fkv_internal.h"
+#include "fkv_select_common.h"
 
 namespace fkv {
-
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kMaxKpt = 32;                       // keys per thread per chunk (8, 16 or 32)
-constexpr int kBins = 2048;
-
-// Monotone map fp32 -> uint32 (larger float <=> larger key), valid for any non-NaN input;
-// -0.0 and +0.0 compare equal as floats, so both get the key of +0.0.  No valid key is 0.
-__device__ __forceinline__ uint32_t order_key(float f) {
-  uint32_t u = __float_as_uint(f);
-  if (u == 0x80000000u) u = 0u;
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Key layout of a chunk of 1024*kKpt keys (kKpt keys per thread): wave w owns virtual positions
-// [64 kKpt w, 64 kKpt (w+1)); its q-th 128-bit load covers positions 64 kKpt w + 256 q + 4 lane
-// + {0..3}, so every load instruction reads 1 KiB of consecutive memory.  Position v holds
-// score v - mis (`base` = row pointer - mis is 16-byte aligned); positions outside
-// [mis, mis+P) get key 0.  Short rows use fewer keys per thread: the kernel is bound by the
-// instructions it spends per key slot.
-template <int kKpt>
-__device__ __forceinline__ int slot_pos(int wave, int lane, int q) { return wave * (64 * kKpt) + q * 256 + lane * 4; }
-
-template <int kKpt>
-__device__ __forceinline__ void load_keys(const float *base, int mis, int P, int v_chunk, int wave, int lane,
-                                          uint32_t (&key)[kKpt]) {
-  typedef float f32x4 __attribute__((ext_vector_type(4)));
-#pragma unroll
-  for (int q = 0; q < kKpt / 4; ++q) {
-    const int v = v_chunk + slot_pos<kKpt>(wave, lane, q);
-    if (v >= mis && v + 3 < mis + P) {
-      const f32x4 f = *reinterpret_cast<const f32x4 *>(base + v);
-      key[4 * q + 0] = order_key(f[0]);
-      key[4 * q + 1] = order_key(f[1]);
-      key[4 * q + 2] = order_key(f[2]);
-      key[4 * q + 3] = order_key(f[3]);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int vv = v + e;
-        key[4 * q + e] = (vv >= mis && vv < mis + P) ? order_key(base[vv]) : 0u;
-      }
-    }
-  }
-}
-
-__device__ __forceinline__ void wave_sync_lds() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 template <bool kResident, int kKpt>
 __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32_t *out, uint32_t *hist,
@@ -115,36 +64,13 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   // Picks the histogram bin that holds the `remaining`-th largest candidate and narrows the
   // interval to it.  Expects hist filled and a barrier passed; leaves a barrier behind.
   auto narrow = [&](int shift) {
-    // thread owns bins 2*tid, 2*tid+1; suffix sums from the top bin down
-    const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
-    const uint32_t mine = h0 + h1;
-    uint32_t run = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t v = __shfl_down(run, off);
-      if (lane + off < 64) run += v;
-    }
-    if (lane == 0) wsum[wave] = run;
-    __syncthreads();
-    uint32_t above = run - mine;
-    for (int w = wave + 1; w < kSelWaves; ++w) above += wsum[w];
-    if (above < remaining && remaining <= above + mine) {
-      const bool top = remaining <= above + h1;
-      const uint32_t digit = 2 * tid + (top ? 1 : 0);
-      const uint32_t in_bin = top ? h1 : h0;
-      const uint32_t rem = remaining - above - (top ? 0u : h1);
-      bcast[0] = lo + (digit << shift);
-      bcast[1] = rem;
-      bcast[2] = (in_bin == rem) ? 1u : 0u;  // the whole bin is kept: no need to refine further
-      bcast[3] = in_bin;
-    }
-    __syncthreads();
-    lo = bcast[0];
-    remaining = bcast[1];
+    const BinPick p = pick_bin(hist, wsum, bcast, remaining);
+    lo += p.digit << shift;
+    remaining = p.remaining;
     need_eq = remaining;
     s = shift;
-    whole_bin = bcast[2] != 0u;
-    return bcast[3];  // candidates left
+    whole_bin = p.in_bin == p.remaining;  // the whole bin is kept: no need to refine further
+    return p.in_bin;                      // candidates left
   };
   auto clear_hist = [&]() {
     __syncthreads();  // wsum / hist / bcast readers of the previous round are done
@@ -232,99 +158,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   uint32_t run_gt = 0, run_eq = 0;
   for (int ch = 0; ch < n_chunks; ++ch) {
     if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
-    uint32_t cnt[kQ];   // per 4-key item: keys > T (low 16 bits), keys == T (high 16 bits)
-#pragma unroll
-    for (int q = 0; q < kQ; ++q) {
-      uint32_t c = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) c += (key[4 * q + e] > T ? 1u : 0u) + (key[4 * q + e] == T ? 0x10000u : 0u);
-      cnt[q] = c;
-    }
-    // Kept counts per (q, lane) item, packed (low 16 bits: keys > T, high 16 bits: keys == T).
-    // Index order inside the wave is item order q*64 + lane; lane l scans items 8l .. 8l+7 from a
-    // wave-private LDS table, the 64 lanes scan their sums, and the table is overwritten with the
-    // exclusive prefix of every item.
-    FKV_TICK(4);
-    uint32_t *tbl = scan_tbl + wave * (64 * kMaxKpt);  // 64*kQ table entries, then up to 64*kKpt staged outputs
-#pragma unroll
-    for (int q = 0; q < kQ; ++q) tbl[q * 64 + lane] = cnt[q];
-    wave_sync_lds();
-    uint32_t item[kQ];
-#pragma unroll
-    for (int i = 0; i < kQ; ++i) item[i] = tbl[kQ * lane + i];
-    uint32_t mine = 0;
-#pragma unroll
-    for (int i = 0; i < kQ; ++i) mine += item[i];
-    uint32_t inc = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t v = (uint32_t)__shfl_up((int)inc, off);
-      if (lane >= off) inc += v;
-    }
-    const uint32_t wave_tot = (uint32_t)__shfl((int)inc, 63);
-    uint32_t pre = inc - mine;
-    wave_sync_lds();
-#pragma unroll
-    for (int i = 0; i < kQ; ++i) {
-      tbl[kQ * lane + i] = pre;
-      pre += item[i];
-    }
-    FKV_TICK(5);
-    __syncthreads();  // wsum is free (previous readers are past their loop); tables are complete
-    if (lane == 0) wsum[wave] = wave_tot;
-    __syncthreads();
-    uint32_t before_w = 0, total = 0;
-    for (int w = 0; w < kSelWaves; ++w) {
-      const uint32_t v = wsum[w];
-      if (w < wave) before_w += v;
-      total += v;
-    }
-    FKV_TICK(6);
-    // Kept indices are first placed in the wave's LDS region (its outputs are consecutive in the
-    // result because index order is kept), then written out with full 64-lane stores.
-    uint32_t pq[kQ];
-#pragma unroll
-    for (int q = 0; q < kQ; ++q) pq[q] = tbl[q * 64 + lane];
-    wave_sync_lds();  // every lane holds its prefixes: the region can be reused for staging
-    const uint32_t gt0 = run_gt + (before_w & 0xFFFFu), eq0 = run_eq + (before_w >> 16);
-    const uint32_t wave_base = gt0 + min(eq0, need_eq);
-    const uint32_t wave_end = gt0 + (wave_tot & 0xFFFFu) + min(eq0 + (wave_tot >> 16), need_eq);
-    int32_t *stg = reinterpret_cast<int32_t *>(tbl);
-    int32_t *dummy = reinterpret_cast<int32_t *>(bcast) + 8 + lane;  // sink for keys that are dropped
-    const int i_chunk = ch * kChunk - mis;
-#pragma unroll
-    for (int q = 0; q < kQ; ++q) {
-      uint32_t gt_before = gt0 + (pq[q] & 0xFFFFu);
-      uint32_t eq_before = eq0 + (pq[q] >> 16);
-      const int i0 = i_chunk + slot_pos<kKpt>(wave, lane, q);
-      if ((cnt[q] >> 16) == 0) {
-        // no key of this item ties with T: branch-free placement
-        int32_t *dst = stg + (gt_before + min(eq_before, need_eq) - wave_base);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bool kept = key[4 * q + e] > T;
-          *(kept ? dst : dummy) = i0 + e;
-          dst += kept ? 1 : 0;
-        }
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const uint32_t kk = key[4 * q + e];
-          if (kk > T) {
-            stg[gt_before + min(eq_before, need_eq) - wave_base] = i0 + e;
-            ++gt_before;
-          } else if (kk == T) {
-            if (eq_before < need_eq) stg[gt_before + eq_before - wave_base] = i0 + e;
-            ++eq_before;
-          }
-        }
-      }
-    }
-    wave_sync_lds();
-    for (uint32_t o = lane; o < wave_end - wave_base; o += 64) out[wave_base + o] = stg[o];
-    __syncthreads();  // the tables are rewritten by the next chunk
-    run_gt += total & 0xFFFFu;
-    run_eq += total >> 16;
+    compact_chunk<kKpt>(key, T, need_eq, run_gt, run_eq, ch * kChunk - mis, out, scan_tbl, wsum, bcast + 8);
   }
   FKV_TICK(3);
 }
