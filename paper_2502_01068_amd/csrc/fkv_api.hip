@@ -18,7 +18,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-  size_t partial, rowstat, scores_group, scores_tsp, counters, bpartial, cpartial, total;
+  size_t partial, rowstat, scores_group, scores_tsp, counters, bpartial, cpartial, sel_long, total;
   int max_stat_blocks;
 };
 
@@ -34,6 +34,7 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
   w.counters = off;     off += align_up((size_t)kNumCounters * sizeof(unsigned));
   w.bpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxFusedBlocks * sizeof(float2));
   w.cpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxClusters * sizeof(float2));
+  w.sel_long = off;     off += align_up((size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
   w.total = off;
   return w;
 }
@@ -395,6 +396,7 @@ int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_
   memset(c->n_acc, 0, sizeof c->n_acc);
   e = hipMalloc(reinterpret_cast<void **>(&c->ws), c->lay.total);
   if (e == hipSuccess) e = hipMemset(c->ws + c->lay.counters, 0, kNumCounters * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(c->ws + c->lay.sel_long, 0, (size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
   if (e != hipSuccess) {
     if (c->ws) (void)hipFree(c->ws);
     delete c;
@@ -448,7 +450,7 @@ int fkv_select_topk(fkv_ctx *ctx, const fkv_shape *shape, const float *scores, i
   fill_rowset(&a.set[0], scores, r.sum_p, n_rows, idx_out, off, r.n_seq);
   hipStream_t st = static_cast<hipStream_t>(stream);
   Timed t(ctx, st, KID_SELECT);
-  const hipError_t e = launch_select(a, st);
+  const hipError_t e = launch_select(a, reinterpret_cast<uint32_t *>(ctx->ws + ctx->lay.sel_long), st);
   return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 
@@ -533,7 +535,7 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
   if (tsp) fill_rowset(&a.set[a.n_sets++], stp, r.sum_p, 1, idx_tsp, off_tsp, r.n_seq);
   {
     Timed t(ctx, st, KID_SELECT);
-    const hipError_t e = launch_select(a, st);
+    const hipError_t e = launch_select(a, reinterpret_cast<uint32_t *>(ctx->ws + ctx->lay.sel_long), st);
     if (e != hipSuccess) return hip_fail(e);
   }
 

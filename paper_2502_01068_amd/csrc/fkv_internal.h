@@ -107,14 +107,25 @@ struct SelectRowSet {
   int32_t *idx_out;     // [n_rows][cnt_off[n_seq]]
   int cnt_off[FKV_MAX_SEQS + 1];  // prefix sums of the per-sequence keep counts
 };
+// Rows longer than 32768 keys are selected by a chain of launches that keeps per-row state here.
+constexpr int kLongMaxInst = 64;     // (row, sequence) instances one call may have on that path
+constexpr int kLongMaxSlices = 1024; // 8192-key slices per row (8.4M keys)
+constexpr int kLongInfo = 3 * 2048;  // words: [3][2048] histograms, 16 info words, 2 counts per slice
+constexpr int kLongCnt = kLongInfo + 16;
+constexpr int kLongStateWords = kLongCnt + 2 * kLongMaxSlices;
 struct SelectArgs {
   SelectRowSet set[2];
   int n_sets;
   int W;
   int n_seq;
   int cu[FKV_MAX_SEQS + 1];
+  uint32_t *long_state;  // [kLongMaxInst][kLongStateWords], or nullptr: long rows stay on the one-block kernel
 };
-hipError_t launch_select(const SelectArgs &a, hipStream_t s);
+// `long_state` is the context's state buffer for rows over 32768 keys (may be nullptr).
+hipError_t launch_select(SelectArgs a, uint32_t *long_state, hipStream_t s);
+int select_long_chunk(void);
+int select_long_threshold(void);
+hipError_t launch_select_long(const SelectArgs &a, int rows, int max_slices, hipStream_t s);
 
 // ---- gather -----------------------------------------------------------------------------
 struct GatherJob {

@@ -181,6 +181,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
   const float *sc = rs.scores + (size_t)row * rs.row_stride + (a.cu[b] - b * a.W);
   int32_t *out = rs.idx_out + (size_t)row * rs.cnt_off[a.n_seq] + rs.cnt_off[b];
 
+  if (a.long_state != nullptr && P + 3 > kSelThreads * kMaxKpt) return;  // taken by the multi-block chain
   if ((int)threadIdx.x < a.W) out[kp + threadIdx.x] = P + threadIdx.x;  // window tokens are always kept
   if (kp <= 0) return;
   if (P + 3 <= kSelThreads * 8)
@@ -193,11 +194,29 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
     select_row<false, 32>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
 }
 
-hipError_t launch_select(const SelectArgs &a, hipStream_t s) {
+hipError_t launch_select(SelectArgs a, uint32_t *long_state, hipStream_t s) {
   int rows = 0;
   for (int i = 0; i < a.n_sets; ++i) rows += a.set[i].n_rows;
-  hipLaunchKernelGGL(k_select, dim3(rows, a.n_seq), dim3(kSelThreads), 0, s, a);
-  return hipGetLastError();
+  // Rows over one chunk go to the multi-block chain when the call's row instances fit its state.
+  int max_slices = 0;
+  bool any_short = false;
+  for (int b = 0; b < a.n_seq; ++b) {
+    const int P = a.cu[b + 1] - a.cu[b] - a.W;
+    if (P + 3 > select_long_threshold())
+      max_slices = max(max_slices, (P + 3 + select_long_chunk() - 1) / select_long_chunk());
+    else
+      any_short = true;
+  }
+  const bool use_long = long_state != nullptr && max_slices > 0 && max_slices <= kLongMaxSlices &&
+                        (int64_t)rows * a.n_seq <= kLongMaxInst;
+  a.long_state = use_long ? long_state : nullptr;
+  hipError_t e = hipSuccess;
+  if (!use_long || any_short) {
+    hipLaunchKernelGGL(k_select, dim3(rows, a.n_seq), dim3(kSelThreads), 0, s, a);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess && use_long) e = launch_select_long(a, rows, max_slices, s);
+  return e;
 }
 
 }  // namespace fkv
