@@ -21,7 +21,9 @@
  *     stream).  Calls never synchronise, never allocate, and validate every argument on
  *     the host before the first launch, so a rejected call has no effect.
  *   - Two calls that share a context must be ordered on one stream (they share the
- *     context's workspace).
+ *     context's workspace).  Calls on different contexts may run concurrently on different
+ *     streams; while several contexts exist on a device, their single-pass score launches are
+ *     chained on the GPU through an event (that event wait cannot be captured into a graph).
  *   - bf16 tensors are raw 16-bit patterns.  Scores are fp32, indices int32.
  *
  * Tensor layouts (B = n_seq sequences packed along tokens, T_b = cu_seqlens[b], sum L = T_B)

@@ -2,6 +2,7 @@
 // Every entry point validates on the host first, then only enqueues kernels on the caller's
 // stream; nothing here synchronises or allocates after fkv_create.
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <string.h>
 #include <vector>
@@ -38,6 +39,18 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
   w.total = off;
   return w;
 }
+
+// The single-pass score kernel needs its whole grid resident at once (one block per CU).  Two such
+// launches from different streams could each get part of the CUs and wait for the rest forever, so
+// when more than one context lives on a device their single-pass launches are chained on the GPU
+// through an event (no host wait): each waits for the previous one to finish.
+struct FusedGate {
+  std::mutex mu;
+  int n_ctx = 0;
+  hipEvent_t last = nullptr;
+  bool recorded = false;
+};
+FusedGate g_gate[16];
 
 struct EventPair { hipEvent_t a, b, start; int kid; };  // start = own `a` or the previous launch's `b`
 
@@ -220,8 +233,19 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
       f.n_wg = total;
       f.n_clusters = clusters;
       f.timeout_ticks = 200000000ull;  // 2 s
-      Timed t(ctx, st, KID_SCORE_FUSED);
-      const hipError_t e = launch_score_fused(a, f, st);
+      FusedGate &gate = g_gate[ctx->device & 15];
+      std::lock_guard<std::mutex> lock(gate.mu);
+      const bool chained = gate.n_ctx > 1 && gate.last != nullptr;
+      hipError_t e = hipSuccess;
+      if (chained && gate.recorded) e = hipStreamWaitEvent(st, gate.last, 0);
+      if (e == hipSuccess) {
+        Timed t(ctx, st, KID_SCORE_FUSED);
+        e = launch_score_fused(a, f, st);
+      }
+      if (e == hipSuccess && chained) {
+        e = hipEventRecord(gate.last, st);
+        gate.recorded = true;
+      }
       return e == hipSuccess ? FKV_OK : hip_fail(e);
     }
     if (r.sum_p == 0) return FKV_OK;  // no prefix token anywhere: nothing to score
@@ -395,9 +419,20 @@ int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_
   memset(c->ms_acc, 0, sizeof c->ms_acc);
   memset(c->n_acc, 0, sizeof c->n_acc);
   e = hipMalloc(reinterpret_cast<void **>(&c->ws), c->lay.total);
+  {
+    FusedGate &gate = g_gate[device & 15];
+    std::lock_guard<std::mutex> lock(gate.mu);
+    if (e == hipSuccess && gate.last == nullptr) e = hipEventCreateWithFlags(&gate.last, hipEventDisableTiming);
+    if (e == hipSuccess) ++gate.n_ctx;
+  }
+  const bool counted = e == hipSuccess;
   if (e == hipSuccess) e = hipMemset(c->ws + c->lay.counters, 0, kNumCounters * sizeof(unsigned));
   if (e == hipSuccess) e = hipMemset(c->ws + c->lay.sel_long, 0, (size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
   if (e != hipSuccess) {
+    if (counted) {
+      std::lock_guard<std::mutex> lock(g_gate[device & 15].mu);
+      --g_gate[device & 15].n_ctx;
+    }
     if (c->ws) (void)hipFree(c->ws);
     delete c;
     return hip_fail(e);
@@ -411,6 +446,10 @@ int fkv_destroy(fkv_ctx *ctx) {
   for (auto &p : ctx->ev_pool) {
     (void)hipEventDestroy(p.a);
     (void)hipEventDestroy(p.b);
+  }
+  {
+    std::lock_guard<std::mutex> lock(g_gate[ctx->device & 15].mu);
+    --g_gate[ctx->device & 15].n_ctx;
   }
   const hipError_t e = hipFree(ctx->ws);
   delete ctx;
