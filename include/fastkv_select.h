@@ -129,6 +129,24 @@ int fkv_gather_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const voi
                   const int32_t *idx_kv, const int32_t *budget_per_seq, void *k_out, void *v_out,
                   void *stream);
 
+/* Per-head variant of the score (Eq. 1 alone, no averaging over heads): scores_head [Hq][sum P]
+ * holds the pooled saliency S^{l,h} of every query head.  With fkv_select_topk (n_rows = Hq) and
+ * fkv_gather_kv_per_head it gives head-wise KV retention, the layout Sec. 5.3 contrasts with the
+ * group-wise one (it stores Hq instead of Hkv compacted copies). */
+int fkv_score_heads(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, float *scores_head,
+                    void *stream);
+
+/* k_out[h][o_b + t][:] = k[T_b + idx_head[h][o_b + t]][h / G][:] for every query head h < Hq (same
+ * for v; v / v_out may both be NULL).  idx_head [Hq][sum budget], k_out, v_out [Hq][sum budget][d]. */
+int fkv_gather_kv_per_head(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const void *v,
+                           const int32_t *idx_head, const int32_t *budget_per_seq, void *k_out, void *v_out,
+                           void *stream);
+
+/* Keep count for a rate ("top-{context length x R}", App. B.1): round-half-up of rate * n_tokens,
+ * at most n_tokens (20 % of 32768 -> 6554); -1 for a negative length or rate.  Host only.  Callers
+ * who read the paper's merge as "top-k plus the window" pass count + W to the calls above. */
+int32_t fkv_count_from_rate(int32_t n_tokens, double rate);
+
 /* compress_kv(K, V, budget): one layer's selection of Algorithm 1 in one call: score once,
  * select budget_b tokens per KV head, gather K/V; and, when x != NULL, also the TSP leg
  * (HiddenCompress): select k_tsp_b tokens on the all-head score and gather hidden rows.

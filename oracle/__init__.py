@@ -160,6 +160,27 @@ def gather_kv(kv, idx_kv):
     return out
 
 
+def gather_kv_per_head(kv, idx_head):
+    """Head-wise KV retention (the layout Sec. 5.3 contrasts with group-wise storage):
+    kv [L,Hkv,d], idx_head [Hq,b] -> [Hq,b,d] with out[h,t] = kv[idx_head[h,t], h // G]."""
+    kv = np.ascontiguousarray(kv)
+    L, Hkv, d = kv.shape
+    idx_head = np.ascontiguousarray(idx_head, dtype=np.int32)
+    Hq, b = idx_head.shape
+    if Hq % Hkv != 0:
+        raise ValueError("Hq must be a multiple of Hkv")
+    if idx_head.size and (idx_head.min() < 0 or idx_head.max() >= L):
+        raise IndexError("gather index out of range")
+    G = Hq // Hkv
+    out = np.empty((Hq, b, d), dtype=kv.dtype)
+    lib = _lib("f32")
+    for h in range(Hq):
+        base = ctypes.c_void_p(kv.ctypes.data + (h // G) * d * kv.itemsize)
+        lib.orc_gather_rows(base, ctypes.c_size_t(kv.strides[0]), ctypes.c_size_t(d * kv.itemsize),
+                            _ptr(idx_head[h]), b, _ptr(out[h]))
+    return out
+
+
 def compress_kv(q_win, k, v, budget, pool_kernel=7, pool_mode="max", scale=None, causal=True,
                 x=None, k_tsp=None, precision="f32", threads=None):
     """One layer of Algorithm 1 for one sequence: KVCompress with `budget` kept tokens per

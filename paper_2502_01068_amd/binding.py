@@ -22,6 +22,7 @@ EXPORTS = [
     "fkv_workspace_bytes", "fkv_create", "fkv_destroy", "fkv_score_window", "fkv_select_topk",
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
+    "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate",
 ]
 
 
@@ -70,6 +71,10 @@ def load():
     lib.fkv_gather_rows.argtypes = [vp, shp, vp, sz, vp, pi32, vp, vp]
     lib.fkv_gather_kv.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
     lib.fkv_compress_kv.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp, vp, sz, pi32, vp, vp, vp]
+    lib.fkv_score_heads.argtypes = [vp, shp, vp, vp, vp, vp]
+    lib.fkv_gather_kv_per_head.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
+    lib.fkv_count_from_rate.restype = i32
+    lib.fkv_count_from_rate.argtypes = [i32, ctypes.c_double]
     lib.fkv_set_score_path.argtypes = [vp, ctypes.c_int]
     lib.fkv_query_error.argtypes = [vp, pi32]
     lib.fkv_profile_kernels.restype = ctypes.c_int
@@ -108,6 +113,11 @@ def make_shape(lengths, n_q_heads=32, n_kv_heads=8, head_dim=128, window=8, pool
     s._keep = arr
     s._lengths = [int(n) for n in lengths]
     return s
+
+
+def fkv_count_from_rate(n_tokens, rate):
+    """Round-half-up keep count for a rate (host only)."""
+    return int(load().fkv_count_from_rate(int(n_tokens), float(rate)))
 
 
 def _check(status, where):
@@ -244,6 +254,29 @@ class Context:
             t_arr if tsp else None, _dev_ptr(out.get("x_out"), "x_out", None, True),
             _dev_ptr(out.get("idx_tsp"), "idx_tsp", (torch.int32,), True), _stream()), "fkv_compress_kv")
         return out
+
+    def fkv_score_heads(self, shape, q_win, k, scores_head=None):
+        """-> scores_head [Hq, sum P] fp32: pooled per-head scores (Eq. 1), no head averaging"""
+        sum_p = sum(shape._lengths) - shape.n_seq * shape.window
+        if scores_head is None:
+            scores_head = torch.empty((shape.n_q_heads, sum_p), dtype=torch.float32, device=k.device)
+        _check(load().fkv_score_heads(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
+                                      _dev_ptr(k, "k", _BF16), _dev_ptr(scores_head, "scores_head", (torch.float32,)),
+                                      _stream()), "fkv_score_heads")
+        return scores_head
+
+    def fkv_gather_kv_per_head(self, shape, k, v, idx_head, budget_per_seq, k_out=None, v_out=None):
+        counts, arr = _counts(shape, budget_per_seq)
+        tot = sum(counts)
+        if k_out is None:
+            k_out = torch.empty((shape.n_q_heads, tot, shape.head_dim), dtype=k.dtype, device=k.device)
+        if v is not None and v_out is None:
+            v_out = torch.empty((shape.n_q_heads, tot, shape.head_dim), dtype=v.dtype, device=v.device)
+        _check(load().fkv_gather_kv_per_head(self.handle, ctypes.byref(shape), _dev_ptr(k, "k", _BF16),
+                                             _dev_ptr(v, "v", _BF16, True), _dev_ptr(idx_head, "idx_head", (torch.int32,)),
+                                             arr, _dev_ptr(k_out, "k_out"), _dev_ptr(v_out, "v_out", None, True),
+                                             _stream()), "fkv_gather_kv_per_head")
+        return k_out, v_out
 
     def fkv_set_score_path(self, mode):
         """0 auto, 1 two-pass kernels, 2 single-pass resident-grid kernel."""

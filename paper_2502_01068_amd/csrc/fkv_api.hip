@@ -179,7 +179,7 @@ void fill_map(const Resolved &r, SeqMap *m) {
 }
 
 int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const void *q_win, const void *k,
-                  float *scores_group, float *scores_tsp, hipStream_t st) {
+                  float *scores_group, float *scores_tsp, float *scores_head, hipStream_t st) {
   ScoreArgs a{};
   a.q_win = static_cast<const uint16_t *>(q_win);
   a.k = static_cast<const uint16_t *>(k);
@@ -188,6 +188,7 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
   a.rowstat = reinterpret_cast<float *>(ctx->ws + ctx->lay.rowstat);
   a.scores_group = scores_group;
   a.scores_tsp = scores_tsp;
+  a.scores_head = scores_head;
   a.Hq = r.Hq; a.Hkv = r.Hkv; a.G = r.G; a.W = r.W;
   const float scale = sh->softmax_scale > 0.f ? sh->softmax_scale : 1.0f / sqrtf((float)sh->head_dim);
   a.scale_log2e = scale * 1.4426950408889634f;
@@ -310,7 +311,8 @@ void fill_rowset(SelectRowSet *rs, const float *scores, int64_t stride, int n_ro
 }
 
 void fill_job(GatherJob *j, const void *src, void *dst, const int32_t *idx, int64_t stride, int row_bytes,
-              int n_heads, const int *off, int n_seq) {
+              int n_heads, const int *off, int n_seq, int head_div = 1) {
+  j->head_div = head_div;
   j->src = static_cast<const uint8_t *>(src);
   j->dst = static_cast<uint8_t *>(dst);
   j->idx = idx;
@@ -465,7 +467,7 @@ int fkv_score_window(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, co
   if (misaligned(q_win) || misaligned(k) || misaligned(scores_group) || misaligned(scores_tsp)) return FKV_EALIGN;
   rc = check_ctx(ctx, r);
   if (rc != FKV_OK) return rc;
-  return enqueue_score(ctx, shape, r, q_win, k, scores_group, scores_tsp, static_cast<hipStream_t>(stream));
+  return enqueue_score(ctx, shape, r, q_win, k, scores_group, scores_tsp, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int fkv_select_topk(fkv_ctx *ctx, const fkv_shape *shape, const float *scores, int32_t n_rows,
@@ -534,6 +536,47 @@ int fkv_gather_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const voi
   return enqueue_gather(ctx, g, r, static_cast<hipStream_t>(stream));
 }
 
+int fkv_score_heads(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, float *scores_head,
+                    void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!q_win || !k || (!scores_head && r.sum_p > 0)) return FKV_ENULL;
+  if (misaligned(q_win) || misaligned(k) || misaligned(scores_head)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  return enqueue_score(ctx, shape, r, q_win, k, nullptr, nullptr, scores_head, static_cast<hipStream_t>(stream));
+}
+
+int fkv_gather_kv_per_head(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const void *v,
+                           const int32_t *idx_head, const int32_t *budget_per_seq, void *k_out, void *v_out,
+                           void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!k || !idx_head || !k_out) return FKV_ENULL;
+  if ((v == nullptr) != (v_out == nullptr)) return FKV_ENULL;
+  int off[FKV_MAX_SEQS + 1];
+  rc = check_counts(r, budget_per_seq, off);
+  if (rc != FKV_OK) return rc;
+  if (misaligned(k) || misaligned(v) || misaligned(k_out) || misaligned(v_out) || misaligned(idx_head)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  const int row_bytes = kHeadDim * 2;
+  GatherArgs g{};
+  g.n_jobs = 0;
+  fill_job(&g.job[g.n_jobs++], k, k_out, idx_head, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hq, off, r.n_seq, r.G);
+  if (v) fill_job(&g.job[g.n_jobs++], v, v_out, idx_head, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hq, off, r.n_seq, r.G);
+  return enqueue_gather(ctx, g, r, static_cast<hipStream_t>(stream));
+}
+
+int32_t fkv_count_from_rate(int32_t n_tokens, double rate) {
+  if (n_tokens < 0 || !(rate >= 0.0)) return -1;
+  const double x = floor(rate * (double)n_tokens + 0.5);
+  if (x > (double)n_tokens) return n_tokens;
+  return (int32_t)x;
+}
+
 int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k,
                     const void *v, const int32_t *budget_per_seq, void *k_out, void *v_out,
                     int32_t *idx_kv, const void *x, size_t x_row_bytes,
@@ -562,7 +605,7 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
   hipStream_t st = static_cast<hipStream_t>(stream);
   float *sg = reinterpret_cast<float *>(ctx->ws + ctx->lay.scores_group);
   float *stp = tsp ? reinterpret_cast<float *>(ctx->ws + ctx->lay.scores_tsp) : nullptr;
-  rc = enqueue_score(ctx, shape, r, q_win, k, sg, stp, st);
+  rc = enqueue_score(ctx, shape, r, q_win, k, sg, stp, nullptr, st);
   if (rc != FKV_OK) return rc;
 
   SelectArgs a{};

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(GatherArgs a) {
   const uint32_t n_chunks = (uint32_t)job.total_rows * cpr; // per head; host guarantees < 2^31
   const uint32_t c0 = hb * (kGatherUnroll * kGatherThreads) + threadIdx.x;
   const int32_t *idx = job.idx + (size_t)h * job.total_rows;
-  const uint8_t *src_h = job.src + (size_t)h * job.row_bytes;
+  const uint8_t *src_h = job.src + (size_t)(h / (uint32_t)job.head_div) * job.row_bytes;
   u32x4 *dst_h = reinterpret_cast<u32x4 *>(job.dst + (size_t)h * job.total_rows * job.row_bytes);
 
   u32x4 val[kGatherUnroll];

@@ -56,7 +56,8 @@ struct ScoreArgs {
   float2 *partial;        // [Hkv*32][partial_stride]: per stats block (running max, sum), log2 units
   int partial_stride;     // blocks the workspace was sized for
   float *rowstat;         // [B][Hkv*32]: log2-domain max + log2(sum) per softmax row
-  float *scores_group;    // [Hkv][sum P]
+  float *scores_group;    // [Hkv][sum P] or nullptr
+  float *scores_head;     // [Hq][sum P] or nullptr: pooled per-head scores before any head averaging
   float *scores_tsp;      // [sum P] or nullptr
   SeqMap map;
   int Hq, Hkv, G, W;
@@ -134,7 +135,8 @@ struct GatherJob {
   const int32_t *idx;     // [n_heads][total_rows]
   int64_t src_row_stride; // bytes between consecutive tokens in src
   int row_bytes;          // bytes copied per (head, kept token); multiple of 16
-  int n_heads;            // src offset of head h inside a token row is h*row_bytes
+  int n_heads;            // output heads; head h reads source head h / head_div
+  int head_div;           // src offset of source head s inside a token row is s*row_bytes
   int total_rows;         // kept rows per head over all sequences
   int blk0;               // first block of this job in the launch
   int blocks_per_head;    // blocks that cover one head's kept rows

@@ -175,10 +175,11 @@ __device__ __forceinline__ void pool_and_write(const ScoreArgs &a, const float (
           for (int t = -r; t <= r; ++t) p += row[t];
           p *= inv_k;
         }
+        if (a.scores_head) a.scores_head[(size_t)(g * a.G + hl) * a.sum_p + col0 + o0 + jj] = p;
         gs += p;
       }
       g_sum[g][jj] = gs;
-      a.scores_group[(size_t)g * a.sum_p + col0 + o0 + jj] = gs * inv_g;
+      if (a.scores_group) a.scores_group[(size_t)g * a.sum_p + col0 + o0 + jj] = gs * inv_g;
     }
   }
   if (a.scores_tsp == nullptr) return;

@@ -134,3 +134,15 @@ def test_workspace_bytes(lib):
     assert 0 < small < big < 64 << 20
     assert big >= 131072 * 9 * 4
     assert lib.fkv_workspace_bytes(0, 1) == 0 and lib.fkv_workspace_bytes(100, 65) == 0
+
+
+def test_count_from_rate_matches_the_stated_counts(lib):
+    # 20 % of 32768 -> 6554 kept, 20 % / 10 % of 131072 -> 26214 / 13107 (round half up, not ceil)
+    assert lib.fkv_count_from_rate(32768, 0.2) == 6554
+    assert lib.fkv_count_from_rate(131072, 0.2) == 26214
+    assert lib.fkv_count_from_rate(131072, 0.1) == 13107
+    assert lib.fkv_count_from_rate(10, 0.25) == 3 and lib.fkv_count_from_rate(10, 0.24) == 2
+    assert lib.fkv_count_from_rate(100, 1.5) == 100 and lib.fkv_count_from_rate(0, 0.2) == 0
+    assert lib.fkv_count_from_rate(-1, 0.2) == -1 and lib.fkv_count_from_rate(10, -0.1) == -1
+    assert lib.fkv_count_from_rate(10, float("nan")) == -1
+    assert lib.fkv_score_heads(None, None, None, None, None, None) == fk.FKV_ENULL

@@ -278,6 +278,34 @@ def test_compress_kv_ragged_batch(ctx):
                  [wl.round_half_up(0.2 * L) for L in lengths], "max", "ragged")
 
 
+@pytest.mark.parametrize("pool_mode", ["max", "avg"])
+def test_per_head_retention(ctx, pool_mode):
+    # head-wise variant: pooled per-head scores (Eq. 1), one index set per query head, per-head K/V copies
+    lengths, W, budget = [900, 2100], 8, [64, 300]
+    print("case: per-head retention", lengths, pool_mode, flush=True)
+    batch = wl.make_batch(12, lengths, n_heavy=6, with_x=False)
+    shape = fk.make_shape(lengths, pool_mode=pool_mode)
+    q, k, v = dev_bf16(batch["q_win"]), dev_bf16(np.concatenate([s["k"] for s in batch["seqs"]])), \
+        dev_bf16(np.concatenate([s["v"] for s in batch["seqs"]]))
+    sh = ctx.fkv_score_heads(shape, q, k)
+    idx = ctx.fkv_select_topk(shape, sh, budget)
+    ko, vo = ctx.fkv_gather_kv_per_head(shape, k, v, idx, budget)
+    sh, idx, ko, vo = sh.cpu().numpy(), idx.cpu().numpy(), host_bits(ko), host_bits(vo)
+    col = o = 0
+    for b, s in enumerate(batch["seqs"]):
+        P = lengths[b] - W
+        ref = oracle.score_window(s["q_win"], s["k"], 7, pool_mode, precision="f64")["p_head"]
+        assert_scores_close(sh[:, col:col + P], ref, "scores_head seq %d" % b)
+        mine = idx[:, o:o + budget[b]]
+        for h in range(32):
+            assert_index_set(mine[h], oracle.select_topk(ref[h].astype(np.float32), W, budget[b]), ref[h], W, "head %d" % h)
+            np.testing.assert_array_equal(mine[h], oracle.select_topk(sh[h, col:col + P], W, budget[b]))
+        np.testing.assert_array_equal(ko[:, o:o + budget[b]], oracle.gather_kv_per_head(s["k"], mine))
+        np.testing.assert_array_equal(vo[:, o:o + budget[b]], oracle.gather_kv_per_head(s["v"], mine))
+        col += P
+        o += budget[b]
+
+
 def test_deterministic(ctx):
     print("case: determinism", flush=True)
     s = wl.make_sequence(4, 3000, n_heavy=30)

@@ -309,6 +309,16 @@ def test_gather_matches_library_and_composes():
         oracle.gather_rows(x, np.array([300], np.int32))
 
 
+def test_gather_kv_per_head_matches_library():
+    rng = np.random.default_rng(13)
+    kv = rng.integers(0, 65536, size=(40, 2, 8), dtype=np.uint16)
+    idx = np.stack([np.sort(rng.choice(40, 5, replace=False)) for _ in range(6)]).astype(np.int32)
+    out = oracle.gather_kv_per_head(kv, idx)
+    for h in range(6):
+        ref = torch.index_select(torch.from_numpy(kv[:, h // 3].astype(np.int32)), 0, torch.from_numpy(idx[h]).long())
+        np.testing.assert_array_equal(out[h], ref.numpy().astype(np.uint16))
+
+
 def test_compress_kv_composition_and_heavy_recall():
     s = wl.make_sequence(5, 1024, n_heavy=32)
     out = oracle.compress_kv(s["q_win"], s["k"], s["v"], 128, 7, "max", x=s["x"], k_tsp=256)
