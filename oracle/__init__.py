@@ -181,6 +181,33 @@ def gather_kv_per_head(kv, idx_head):
     return out
 
 
+def decode_attention(q, k, v, layout="compact", scale=None, precision="f32"):
+    """Attention output of one new query token over a KV cache (the decoding step that reads the
+    compressed cache, Algorithm 1 / Sec. 5.3).  q [Hq,d]; layout "compact": k, v [Hkv,n,d] (what
+    KVCompress produced), "token_major": k, v [n,Hkv,d].  Returns [Hq,d] in the chosen precision."""
+    q, k, v = _u16(q, 2), _u16(k, 3), _u16(v, 3)
+    Hq, d = q.shape
+    if layout == "compact":
+        Hkv, n, d2 = k.shape
+        tok_stride, head_stride = d2, n * d2
+    elif layout == "token_major":
+        n, Hkv, d2 = k.shape
+        tok_stride, head_stride = Hkv * d2, d2
+    else:
+        raise ValueError("layout must be 'compact' or 'token_major'")
+    if d2 != d or v.shape != k.shape:
+        raise ValueError("shape mismatch")
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty((Hq, d), dtype=_real(precision))
+    rc = _lib(precision).orc_decode_attention(_ptr(q), _ptr(k), _ptr(v), int(n), Hq, Hkv, d,
+                                              ctypes.c_long(tok_stride), ctypes.c_long(head_stride),
+                                              ctypes.c_double(scale), _ptr(out))
+    if rc != 0:
+        raise ValueError("orc_decode_attention failed: %d" % rc)
+    return out
+
+
 def compress_kv(q_win, k, v, budget, pool_kernel=7, pool_mode="max", scale=None, causal=True,
                 x=None, k_tsp=None, precision="f32", threads=None):
     """One layer of Algorithm 1 for one sequence: KVCompress with `budget` kept tokens per

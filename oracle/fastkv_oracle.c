@@ -183,3 +183,38 @@ int orc_gather_rows(const uint8_t *src, size_t src_stride_bytes, size_t row_byte
     memcpy(out + (size_t)t * row_bytes, src + (size_t)idx[t] * src_stride_bytes, row_bytes);
   return 0;
 }
+
+/* Decode-step attention over a (compressed) KV cache: the consumer of what KVCompress keeps
+ * (Algorithm 1 returns the cache C; Sec. 5.3 measures decoding over it).  One new query token,
+ * every cached token visible: out[h] = sum_t softmax_t(scale * q[h].k[g(h),t]) * v[g(h),t].
+ * q [Hq][d] bf16 bits; k, v addressed as base + t*tok_stride + g*head_stride (in elements), so both
+ * the compacted [Hkv][n][d] and the token-major [n][Hkv][d] layouts fit; out [Hq][d]. */
+int orc_decode_attention(const uint16_t *q, const uint16_t *k, const uint16_t *v, int n, int Hq, int Hkv, int d,
+                         long tok_stride, long head_stride, double scale, real *out) {
+  if (n < 1 || Hq % Hkv != 0) return -1;
+  const int G = Hq / Hkv;
+  const real sc = (real)scale;
+  real *p = (real *)malloc((size_t)n * sizeof(real));
+  if (!p) return -2;
+  for (int h = 0; h < Hq; ++h) {
+    const int g = h / G;
+    real m = 0;
+    for (int t = 0; t < n; ++t) {
+      const uint16_t *kv = k + (size_t)t * tok_stride + (size_t)g * head_stride;
+      real acc = 0;
+      for (int c = 0; c < d; ++c) acc += (real)bf16_to_f32(q[(size_t)h * d + c]) * (real)bf16_to_f32(kv[c]);
+      p[t] = sc * acc;
+      if (t == 0 || p[t] > m) m = p[t];
+    }
+    real Z = 0;
+    for (int t = 0; t < n; ++t) { p[t] = REAL_EXP(p[t] - m); Z += p[t]; }
+    for (int c = 0; c < d; ++c) {
+      real acc = 0;
+      for (int t = 0; t < n; ++t)
+        acc += (p[t] / Z) * (real)bf16_to_f32(v[(size_t)t * tok_stride + (size_t)g * head_stride + c]);
+      out[(size_t)h * d + c] = acc;
+    }
+  }
+  free(p);
+  return 0;
+}

@@ -332,6 +332,48 @@ def test_compress_kv_composition_and_heavy_recall():
     assert recall > 0.8
 
 
+# ----------------------------------------------------------------------------- decode over the cache
+
+@pytest.mark.parametrize("layout", ["compact", "token_major"])
+def test_decode_attention_matches_library(layout):
+    rng = np.random.default_rng(21)
+    Hq, Hkv, d, n = 6, 2, 16, 37
+    q = _rand_bf16(rng, (Hq, d), 1.5)
+    k = _rand_bf16(rng, (Hkv, n, d), 1.5)
+    v = _rand_bf16(rng, (Hkv, n, d))
+    qf, kf, vf = (torch.from_numpy(wl.bf16_bits_to_f32(a)).double() for a in (q, k, v))
+    for scale in (None, 0.3):
+        sc = 1 / math.sqrt(d) if scale is None else scale
+        att = torch.softmax(torch.einsum("hc,htc->ht", qf, kf.repeat_interleave(3, 0)) * sc, dim=-1)
+        ref = torch.einsum("ht,htc->hc", att, vf.repeat_interleave(3, 0)).numpy()
+        kk, vv = (k, v) if layout == "compact" else (np.ascontiguousarray(k.transpose(1, 0, 2)),
+                                                      np.ascontiguousarray(v.transpose(1, 0, 2)))
+        np.testing.assert_allclose(oracle.decode_attention(q, kk, vv, layout, scale, "f64"), ref, rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(oracle.decode_attention(q, kk, vv, layout, scale, "f32"), ref, rtol=2e-4, atol=2e-5)
+
+
+def test_decode_attention_closed_forms():
+    rng = np.random.default_rng(22)
+    Hq, Hkv, d, n = 4, 2, 8, 9
+    q = _rand_bf16(rng, (Hq, d))
+    v = _rand_bf16(rng, (Hkv, n, d))
+    vf = wl.bf16_bits_to_f32(v).astype(np.float64)
+    # equal keys: uniform weights, the output is the mean of the group's value rows
+    out = oracle.decode_attention(q, np.zeros((Hkv, n, d), np.uint16), v, precision="f64")
+    for h in range(Hq):
+        np.testing.assert_allclose(out[h], vf[h // 2].mean(0), rtol=1e-13, atol=1e-15)
+    # a single cached token: the output is its value row exactly
+    out = oracle.decode_attention(q, _rand_bf16(rng, (Hkv, 1, d)), v[:, :1], precision="f32")
+    for h in range(Hq):
+        np.testing.assert_array_equal(out[h], wl.bf16_bits_to_f32(v[h // 2, 0]))
+    # one key far more aligned with the query than the others: the output approaches its value row
+    k = np.zeros((Hkv, n, d), np.float32)
+    qf = wl.bf16_bits_to_f32(q)
+    k[0, 4] = 40 * qf[0]
+    out = oracle.decode_attention(q, wl.f32_to_bf16_bits(k), v, scale=1.0, precision="f64")
+    np.testing.assert_allclose(out[0], vf[0, 4], atol=1e-6)
+
+
 def test_paper_identities():
     g = _gold()
     n_layers, tsp_layer, rate = int(g["n_layers_llama"]), int(g["tsp_layer_llama"]), float(g["tsp_rate"])
