@@ -147,6 +147,18 @@ int fkv_gather_kv_per_head(fkv_ctx *ctx, const fkv_shape *shape, const void *k, 
  * who read the paper's merge as "top-k plus the window" pass count + W to the calls above. */
 int32_t fkv_count_from_rate(int32_t n_tokens, double rate);
 
+/* Decode-step attention of one new query token per sequence over a KV cache, every cached token
+ * visible (the consumer of the compressed cache C of Algorithm 1; Sec. 5.3 measures decoding over
+ * it): out[b][h][:] = sum_t softmax_t(scale * q[b][h].k[b][h/G][t]) * v[b][h/G][t].
+ * q [B][Hq][d] bf16; out [B][Hq][d] fp32; n_per_seq host [B], each >= 1 (the window and any tokens
+ * appended since are simply more cached tokens).  kv_layout FKV_KV_COMPACT: k, v [Hkv][sum n][d],
+ * sequence b at token offset sum_{b'<b} n_b' (the k_out / v_out of fkv_compress_kv);
+ * FKV_KV_TOKEN_MAJOR: k, v [sum n][Hkv][d] (an uncompressed cache).  Only n_seq, the head counts
+ * and softmax_scale of `shape` are used. */
+enum { FKV_KV_COMPACT = 0, FKV_KV_TOKEN_MAJOR = 1 };
+int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,
+                         int32_t kv_layout, const int32_t *n_per_seq, float *out, void *stream);
+
 /* compress_kv(K, V, budget): one layer's selection of Algorithm 1 in one call: score once,
  * select budget_b tokens per KV head, gather K/V; and, when x != NULL, also the TSP leg
  * (HiddenCompress): select k_tsp_b tokens on the all-head score and gather hidden rows.

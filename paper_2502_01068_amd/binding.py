@@ -22,7 +22,7 @@ EXPORTS = [
     "fkv_workspace_bytes", "fkv_create", "fkv_destroy", "fkv_score_window", "fkv_select_topk",
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
-    "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate",
+    "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
 ]
 
 
@@ -73,6 +73,7 @@ def load():
     lib.fkv_compress_kv.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp, vp, sz, pi32, vp, vp, vp]
     lib.fkv_score_heads.argtypes = [vp, shp, vp, vp, vp, vp]
     lib.fkv_gather_kv_per_head.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
+    lib.fkv_decode_attention.argtypes = [vp, shp, vp, vp, vp, i32, pi32, vp, vp]
     lib.fkv_count_from_rate.restype = i32
     lib.fkv_count_from_rate.argtypes = [i32, ctypes.c_double]
     lib.fkv_set_score_path.argtypes = [vp, ctypes.c_int]
@@ -277,6 +278,18 @@ class Context:
                                              arr, _dev_ptr(k_out, "k_out"), _dev_ptr(v_out, "v_out", None, True),
                                              _stream()), "fkv_gather_kv_per_head")
         return k_out, v_out
+
+    def fkv_decode_attention(self, shape, q, k, v, n_per_seq, layout="compact", out=None):
+        """q [B,Hq,d] bf16; k, v [Hkv,sum n,d] ("compact") or [sum n,Hkv,d] ("token_major") -> out [B,Hq,d] fp32"""
+        counts, arr = [int(c) for c in ([n_per_seq] * shape.n_seq if isinstance(n_per_seq, int) else n_per_seq)], None
+        arr = _i32_array(counts)
+        if out is None:
+            out = torch.empty((shape.n_seq, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device=q.device)
+        lay = {"compact": 0, "token_major": 1}[layout]
+        _check(load().fkv_decode_attention(self.handle, ctypes.byref(shape), _dev_ptr(q, "q", _BF16),
+                                           _dev_ptr(k, "k", _BF16), _dev_ptr(v, "v", _BF16), lay, arr,
+                                           _dev_ptr(out, "out", (torch.float32,)), _stream()), "fkv_decode_attention")
+        return out
 
     def fkv_set_score_path(self, mode):
         """0 auto, 1 two-pass kernels, 2 single-pass resident-grid kernel."""

@@ -19,7 +19,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-  size_t partial, rowstat, scores_group, scores_tsp, counters, bpartial, cpartial, sel_long, total;
+  size_t partial, rowstat, scores_group, scores_tsp, counters, bpartial, cpartial, sel_long, dec_part, total;
   int max_stat_blocks;
 };
 
@@ -36,6 +36,7 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
   w.bpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxFusedBlocks * sizeof(float2));
   w.cpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxClusters * sizeof(float2));
   w.sel_long = off;     off += align_up((size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
+  w.dec_part = off;     off += align_up((size_t)max_seqs * kMaxKvHeads * kMaxGroup * kDecodeMaxSplits * (kHeadDim + 2) * sizeof(float));
   w.total = off;
   return w;
 }
@@ -74,7 +75,7 @@ struct fkv_ctx {
 
 namespace {
 
-const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather", "k_score_fused"};
+const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather", "k_score_fused", "k_decode"};
 
 int hip_fail(hipError_t e) {
   g_last_hip_error = (int)e;
@@ -575,6 +576,48 @@ int32_t fkv_count_from_rate(int32_t n_tokens, double rate) {
   const double x = floor(rate * (double)n_tokens + 0.5);
   if (x > (double)n_tokens) return n_tokens;
   return (int32_t)x;
+}
+
+int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,
+                         int32_t kv_layout, const int32_t *n_per_seq, float *out, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!q || !k || !v || !n_per_seq || !out) return FKV_ENULL;
+  if (kv_layout != FKV_KV_COMPACT && kv_layout != FKV_KV_TOKEN_MAJOR) return FKV_EINVAL;
+  DecodeArgs a{};
+  int64_t tot = 0;
+  int n_max = 0;
+  a.off[0] = 0;
+  for (int b = 0; b < r.n_seq; ++b) {
+    if (n_per_seq[b] < 1) return FKV_EINVAL;
+    tot += n_per_seq[b];
+    if (tot > INT32_MAX) return FKV_EINVAL;
+    a.off[b + 1] = (int)tot;
+    if (n_per_seq[b] > n_max) n_max = n_per_seq[b];
+  }
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out)) return FKV_EALIGN;
+  if (!ctx) return FKV_ENULL;
+  if (r.n_seq > ctx->max_seqs) return FKV_EWORKSPACE;
+  ctx->ev_prev = nullptr;
+  a.q = static_cast<const uint16_t *>(q);
+  a.k = static_cast<const uint16_t *>(k);
+  a.v = static_cast<const uint16_t *>(v);
+  a.out = out;
+  a.part = reinterpret_cast<float *>(ctx->ws + ctx->lay.dec_part);
+  a.tok_stride = kv_layout == FKV_KV_COMPACT ? kHeadDim : (int64_t)r.Hkv * kHeadDim;
+  a.head_stride = kv_layout == FKV_KV_COMPACT ? tot * kHeadDim : kHeadDim;
+  a.Hq = r.Hq; a.Hkv = r.Hkv; a.G = r.G; a.n_seq = r.n_seq;
+  int splits = (n_max + 127) / 128;
+  if (splits < 1) splits = 1;
+  if (splits > decode_max_splits()) splits = decode_max_splits();
+  a.n_split = splits;
+  const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->head_dim);
+  a.scale_log2e = scale * 1.4426950408889634f;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timed t(ctx, st, KID_DECODE);
+  const hipError_t e = launch_decode(a, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 
 int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k,

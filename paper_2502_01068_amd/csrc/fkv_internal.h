@@ -39,7 +39,7 @@ extern __device__ unsigned long long fkv_block_ticks[1024 * 4];
 #endif
 
 // Kernel ids for the per-kernel timing facility.
-enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_SCORE_FUSED, KID_COUNT };
+enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_SCORE_FUSED, KID_DECODE, KID_COUNT };
 
 // Sequence map passed by value in the kernel arguments: where each sequence's tokens
 // start and which block range of the launch works on it.
@@ -127,6 +127,21 @@ hipError_t launch_select(SelectArgs a, uint32_t *long_state, hipStream_t s);
 int select_long_chunk(void);
 int select_long_threshold(void);
 hipError_t launch_select_long(const SelectArgs &a, int rows, int max_slices, hipStream_t s);
+
+// ---- decode attention over the cache ----------------------------------------------------
+constexpr int kDecodeMaxSplits = 16;
+struct DecodeArgs {
+  const uint16_t *q;     // [B][Hq][d]
+  const uint16_t *k, *v; // element (b, g, t) at g*head_stride + (off[b] + t)*tok_stride
+  float *out;            // [B][Hq][d]
+  float *part;           // [B][Hq][n_split][d + 2]
+  int64_t tok_stride, head_stride;
+  int Hq, Hkv, G, n_split, n_seq;
+  float scale_log2e;
+  int off[FKV_MAX_SEQS + 1];
+};
+int decode_max_splits(void);
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 
 // ---- gather -----------------------------------------------------------------------------
 struct GatherJob {
