@@ -608,7 +608,7 @@ int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, co
   a.tok_stride = kv_layout == FKV_KV_COMPACT ? kHeadDim : (int64_t)r.Hkv * kHeadDim;
   a.head_stride = kv_layout == FKV_KV_COMPACT ? tot * kHeadDim : kHeadDim;
   a.Hq = r.Hq; a.Hkv = r.Hkv; a.G = r.G; a.n_seq = r.n_seq;
-  int splits = (n_max + 127) / 128;
+  int splits = (n_max + 63) / 64;  // at least 64 tokens per block, at most decode_max_splits() blocks per head
   if (splits < 1) splits = 1;
   if (splits > decode_max_splits()) splits = decode_max_splits();
   a.n_split = splits;

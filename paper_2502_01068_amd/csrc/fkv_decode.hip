@@ -25,6 +25,17 @@ __device__ __forceinline__ void unpack8(const u32x4 &w, float (&f)[8]) {
   f[4] = bf16_lo(w[2]); f[5] = bf16_hi(w[2]); f[6] = bf16_lo(w[3]); f[7] = bf16_hi(w[3]);
 }
 
+// Sum over the 16 lanes of a DPP row (= the lanes that share a token), result in every lane of the
+// row, on the vector ALU (row rotations; no LDS crossbar traffic).  Every lane adds the same pairs
+// at every level, so the 16 results are bit-identical.
+__device__ __forceinline__ float row_sum16(float x) {
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x128, 0xF, 0xF, false));  // row_ror:8
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x124, 0xF, 0xF, false));  // row_ror:4
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x122, 0xF, 0xF, false));  // row_ror:2
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x121, 0xF, 0xF, false));  // row_ror:1
+  return x;
+}
+
 struct DecState {  // running softmax of one head over this lane's tokens, for the lane's 8 columns
   float m, l, acc[8];
 };
@@ -70,30 +81,36 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_partial(DecodeArgs a) {
   const uint16_t *kb = a.k + (size_t)g * a.head_stride + (size_t)a.off[b] * a.tok_stride + c * 8;
   const uint16_t *vb = a.v + (size_t)g * a.head_stride + (size_t)a.off[b] * a.tok_stride + c * 8;
 
-  for (int tb = t0 + wave * 4; tb < t1; tb += kDecWaves * 4) {  // uniform per wave
-    const int t = tb + tq;
-    const bool valid = t < t1;
-    const int tl = valid ? t : t1 - 1;
-    const u32x4 kw = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kb + (size_t)tl * a.tok_stride));
-    const u32x4 vw = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vb + (size_t)tl * a.tok_stride));
-    float kf[8], vf[8];
-    unpack8(kw, kf);
-    unpack8(vw, vf);
+  constexpr int kU = 4;  // token steps whose loads are in flight together
+  for (int tb = t0 + wave * 4; tb < t1; tb += kDecWaves * 4 * kU) {  // uniform per wave
+    u32x4 kw[kU], vw[kU];
 #pragma unroll
-    for (int hl = 0; hl < kMaxGroup; ++hl) {
-      float dot = 0.f;
+    for (int u = 0; u < kU; ++u) {
+      const int t = min(tb + u * kDecWaves * 4 + tq, t1 - 1);
+      kw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kb + (size_t)t * a.tok_stride));
+      vw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vb + (size_t)t * a.tok_stride));
+    }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) dot += qf[hl][i] * kf[i];
+    for (int u = 0; u < kU; ++u) {
+      const bool valid = tb + u * kDecWaves * 4 + tq < t1;
+      float kf[8], vf[8];
+      unpack8(kw[u], kf);
+      unpack8(vw[u], vf);
 #pragma unroll
-      for (int off = 1; off < 16; off <<= 1) dot += __shfl_xor(dot, off);  // the 16 lanes of this token
-      const float z = dot * a.scale_log2e;
-      const float mn = valid ? fmaxf(st[hl].m, z) : st[hl].m;
-      const float corr = dec_exp2(st[hl].m - mn);
-      const float p = valid ? dec_exp2(z - mn) : 0.f;
-      st[hl].l = st[hl].l * corr + p;
+      for (int hl = 0; hl < kMaxGroup; ++hl) {
+        float dot = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) st[hl].acc[i] = st[hl].acc[i] * corr + p * vf[i];
-      st[hl].m = mn;
+        for (int i = 0; i < 8; ++i) dot += qf[hl][i] * kf[i];
+        dot = row_sum16(dot);  // the 16 lanes of this token
+        const float z = dot * a.scale_log2e;
+        const float mn = valid ? fmaxf(st[hl].m, z) : st[hl].m;
+        const float corr = dec_exp2(st[hl].m - mn);
+        const float p = valid ? dec_exp2(z - mn) : 0.f;
+        st[hl].l = st[hl].l * corr + p;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) st[hl].acc[i] = st[hl].acc[i] * corr + p * vf[i];
+        st[hl].m = mn;
+      }
     }
   }
   // merge the 4 token groups of the wave (same columns, lanes 16 and 32 apart), fixed order
@@ -148,26 +165,53 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_partial(DecodeArgs a) {
   }
 }
 
-// grid (Hq, B), 128 threads: thread = output column
-__global__ __launch_bounds__(kHeadDim) void k_decode_combine(DecodeArgs a) {
-  const int h = blockIdx.x, b = blockIdx.y, col = threadIdx.x;
+// grid (Hq, B), 512 threads: 4 split groups x 128 output columns.  Every thread first learns the
+// splits' (max, sum) pairs (one load each, all in flight together), then sums its share of the
+// splits' weighted rows with the loads of a round issued together; the 4 groups meet in LDS.
+__global__ __launch_bounds__(4 * kHeadDim) void k_decode_combine(DecodeArgs a) {
+  __shared__ float w_lds[kDecodeMaxSplits];
+  __shared__ float o_lds[4][kHeadDim];
+  __shared__ float l_tot;
+  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int col = tid & (kHeadDim - 1), grp = tid >> 7;
   const float *src = a.part + ((size_t)b * a.Hq + h) * a.n_split * (kHeadDim + 2);
-  float M = kDecNegBig;
-  for (int s = 0; s < a.n_split; ++s) M = fmaxf(M, src[s * (kHeadDim + 2) + kHeadDim]);
-  float L = 0.f, o = 0.f;
-  for (int s = 0; s < a.n_split; ++s) {
-    const float w = dec_exp2(src[s * (kHeadDim + 2) + kHeadDim] - M);
-    L += src[s * (kHeadDim + 2) + kHeadDim + 1] * w;
-    o += src[s * (kHeadDim + 2) + col] * w;
+  if (tid < 64) {  // one wave: lane = split
+    const bool live = tid < a.n_split;
+    const float m = live ? src[tid * (kHeadDim + 2) + kHeadDim] : kDecNegBig;
+    const float l = live ? src[tid * (kHeadDim + 2) + kHeadDim + 1] : 0.f;
+    float M = m;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+    const float w = dec_exp2(m - M);
+    float L = l * w;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) L += __shfl_xor(L, off);
+    w_lds[tid] = w;
+    if (tid == 0) l_tot = L;
   }
-  a.out[((size_t)b * a.Hq + h) * kHeadDim + col] = o / L;
+  __syncthreads();
+  float o = 0.f;
+  const int per = (a.n_split + 3) / 4;
+  const int s0 = grp * per, s1 = min(a.n_split, s0 + per);
+  for (int sb = s0; sb < s1; sb += 8) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = src[(size_t)min(sb + i, s1 - 1) * (kHeadDim + 2) + col];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (sb + i < s1) o += v[i] * w_lds[sb + i];
+  }
+  o_lds[grp][col] = o;
+  __syncthreads();
+  if (grp == 0)
+    a.out[((size_t)b * a.Hq + h) * kHeadDim + col] = (((o_lds[0][col] + o_lds[1][col]) + o_lds[2][col]) + o_lds[3][col]) / l_tot;
 }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(k_decode_partial, dim3(a.n_split, a.Hkv, a.n_seq), dim3(kDecThreads), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_decode_combine, dim3(a.Hq, a.n_seq), dim3(kHeadDim), 0, s, a);
+  hipLaunchKernelGGL(k_decode_combine, dim3(a.Hq, a.n_seq), dim3(4 * kHeadDim), 0, s, a);
   return hipGetLastError();
 }
 

@@ -129,7 +129,7 @@ int select_long_threshold(void);
 hipError_t launch_select_long(const SelectArgs &a, int rows, int max_slices, hipStream_t s);
 
 // ---- decode attention over the cache ----------------------------------------------------
-constexpr int kDecodeMaxSplits = 16;
+constexpr int kDecodeMaxSplits = 64;
 struct DecodeArgs {
   const uint16_t *q;     // [B][Hq][d]
   const uint16_t *k, *v; // element (b, g, t) at g*head_stride + (off[b] + t)*tok_stride
