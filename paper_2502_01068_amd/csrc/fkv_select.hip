@@ -42,12 +42,9 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
       kmin = min(kmin, key[e] - 1u);  // key 0 (no element) wraps to the largest value
     }
   }
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off));
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off));
-  }
-  if (lane == 0) { wsum[wave] = kmin; wsum[kSelWaves + wave] = kmax; }
+  kmax = wave_max_to_last(kmax);
+  kmin = wave_min_to_last(kmin);
+  if (lane == 63) { wsum[wave] = kmin; wsum[kSelWaves + wave] = kmax; }
   __syncthreads();
   for (int w = 0; w < kSelWaves; ++w) {
     kmin = min(kmin, wsum[w]);

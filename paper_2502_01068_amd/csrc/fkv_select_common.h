@@ -2,6 +2,7 @@
 // the histogram bin search and the ordered compaction of one 1024-thread chunk.
 #pragma once
 
+#include "fkv_dpp.h"
 #include "fkv_internal.h"
 
 namespace fkv {
@@ -68,22 +69,19 @@ struct BinPick {
 // barrier is left behind.  wsum: kSelWaves words, bcast: 4 words of LDS.
 __device__ __forceinline__ BinPick pick_bin(const uint32_t *hist, uint32_t *wsum, uint32_t *bcast, uint32_t remaining) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // thread owns bins 2*tid, 2*tid+1; suffix sums from the top bin down
-  const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+  // thread t owns the bin pair 2*(1023-t), 2*(1023-t)+1: thread order runs from the top bin down, so
+  // an inclusive prefix sum over threads counts the candidates in this pair and above it
+  const int pair = kSelThreads - 1 - tid;
+  const uint32_t h0 = hist[2 * pair], h1 = hist[2 * pair + 1];
   const uint32_t mine = h0 + h1;
-  uint32_t run = mine;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t v = __shfl_down(run, off);
-    if (lane + off < 64) run += v;
-  }
-  if (lane == 0) wsum[wave] = run;
+  const uint32_t run = wave_scan_add(mine);
+  if (lane == 63) wsum[wave] = run;
   __syncthreads();
   uint32_t above = run - mine;
-  for (int w = wave + 1; w < kSelWaves; ++w) above += wsum[w];
+  for (int w = 0; w < wave; ++w) above += wsum[w];
   if (above < remaining && remaining <= above + mine) {
     const bool top = remaining <= above + h1;
-    bcast[0] = 2 * tid + (top ? 1 : 0);
+    bcast[0] = 2 * pair + (top ? 1 : 0);
     bcast[1] = remaining - above - (top ? 0u : h1);
     bcast[2] = top ? h1 : h0;
   }
@@ -128,13 +126,8 @@ __device__ __forceinline__ void compact_chunk(const uint32_t (&key)[kKpt], uint3
     uint32_t mine = 0;
 #pragma unroll
     for (int i = 0; i < kQ; ++i) mine += item[i];
-    uint32_t inc = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t v = (uint32_t)__shfl_up((int)inc, off);
-      if (lane >= off) inc += v;
-    }
-    const uint32_t wave_tot = (uint32_t)__shfl((int)inc, 63);
+    const uint32_t inc = wave_scan_add(mine);
+    const uint32_t wave_tot = wave_last(inc);
     uint32_t pre = inc - mine;
     wave_sync_lds();
 #pragma unroll

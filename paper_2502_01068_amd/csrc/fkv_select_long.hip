@@ -94,15 +94,13 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_long_prep(SelectArgs a) {
     kmax = max(kmax, key[e]);
     nmin = max(nmin, key[e] ? ~key[e] : 0u);
   }
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off));
-    nmin = max(nmin, (uint32_t)__shfl_xor((int)nmin, off));
-  }
-  if (lane == 0) { red[wave] = kmax; red[kSelWaves + wave] = nmin; }
+  kmax = wave_max_to_last(kmax);
+  nmin = wave_max_to_last(nmin);
+  if (lane == 63) { red[wave] = kmax; red[kSelWaves + wave] = nmin; }
   __syncthreads();
   if (tid == 0) {
-    for (int w = 1; w < kSelWaves; ++w) { kmax = max(kmax, red[w]); nmin = max(nmin, red[kSelWaves + w]); }
+    kmax = 0u, nmin = 0u;
+    for (int w = 0; w < kSelWaves; ++w) { kmax = max(kmax, red[w]); nmin = max(nmin, red[kSelWaves + w]); }
     atomicMax(&r.st[kLongInfo + kInfMax], kmax);
     atomicMax(&r.st[kLongInfo + kInfNotMin], nmin);
   }
@@ -173,13 +171,10 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_long_round(SelectArgs a) {
       cg += key[e] > T ? 1u : 0u;
       ce += key[e] == T ? 1u : 0u;
     }
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      cg += (uint32_t)__shfl_xor((int)cg, off);
-      ce += (uint32_t)__shfl_xor((int)ce, off);
-    }
+    cg = wave_sum_to_last(cg);
+    ce = wave_sum_to_last(ce);
     __syncthreads();  // pick_bin's readers of wsum are done
-    if (lane == 0) { wsum[wave] = cg; hist[wave] = ce; }
+    if (lane == 63) { wsum[wave] = cg; hist[wave] = ce; }
     __syncthreads();
     if (tid == 0) {
       uint32_t tg = 0, te = 0;
