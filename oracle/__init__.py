@@ -3,7 +3,8 @@
 numpy front end of ``fastkv_oracle.c``: plain CPU loops for the window-attention
 saliency score (Sec. 4.2, Eq. 1), per-head pooling, group / all-head means (Eq. 2,
 App. B.1), top-k with the window merged in (Sec. 4.2) and the row gathers of
-HiddenCompress / KVCompress (App. B.1, Algorithm 1).  Only tests, the smoke check and
+HiddenCompress / KVCompress (App. B.1, Algorithm 1), the decoding step over a cache and the
+two diagnostics of Sec. 3 (set overlap, mass recall).  Only tests, the smoke check and
 the benchmark's CPU-baseline leg may import this package; it shares nothing with the
 GPU library.
 
@@ -206,6 +207,41 @@ def decode_attention(q, k, v, layout="compact", scale=None, precision="f32"):
     if rc != 0:
         raise ValueError("orc_decode_attention failed: %d" % rc)
     return out
+
+
+def index_overlap(a, b):
+    """Number of indices two kept sets share (Sec. 3.1: the overlap of the critical-token sets of two
+    layers; the overlap ratio is this count over the set size).  a, b: ascending duplicate-free
+    index lists.  Walks both lists once."""
+    a = np.asarray(a).reshape(-1)
+    b = np.asarray(b).reshape(-1)
+    i = j = n = 0
+    while i < a.size and j < b.size:
+        if a[i] == b[j]:
+            n += 1
+            i += 1
+            j += 1
+        elif a[i] < b[j]:
+            i += 1
+        else:
+            j += 1
+    return n
+
+
+def mass_recall(scores, idx):
+    """Share of a score row's total mass that an index set covers (Sec. 3.2: attention recall of
+    a token subset).  scores [P] (non-negative mass per prefix token); idx: kept indices, those
+    outside [0, P) (the window tokens of a kept set) carry no score and are skipped.  fp64 sums;
+    0 when the row has no mass."""
+    scores = np.asarray(scores).reshape(-1)
+    total = 0.0
+    for x in scores:
+        total += float(x)
+    kept = 0.0
+    for j in np.asarray(idx).reshape(-1):
+        if 0 <= j < scores.size:
+            kept += float(scores[j])
+    return kept / total if total > 0.0 else 0.0
 
 
 def compress_kv(q_win, k, v, budget, pool_kernel=7, pool_mode="max", scale=None, causal=True,

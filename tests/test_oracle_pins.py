@@ -332,6 +332,52 @@ def test_compress_kv_composition_and_heavy_recall():
     assert recall > 0.8
 
 
+# ----------------------------------------------------------------------------- diagnostics (Sec. 3)
+
+def test_index_overlap_matches_library_and_sets():
+    rng = np.random.default_rng(31)
+    for n_a, n_b, hi in ((0, 5, 20), (7, 0, 20), (12, 9, 20), (300, 512, 2000), (512, 512, 600)):
+        a = np.sort(rng.choice(hi, n_a, replace=False)).astype(np.int32)
+        b = np.sort(rng.choice(hi, n_b, replace=False)).astype(np.int32)
+        want = len(set(a.tolist()) & set(b.tolist()))
+        assert oracle.index_overlap(a, b) == want == np.intersect1d(a, b).size
+        assert oracle.index_overlap(b, a) == want          # symmetric
+        assert oracle.index_overlap(a, a) == n_a            # a set overlaps itself completely
+    assert oracle.index_overlap(np.arange(0, 40, 2), np.arange(1, 40, 2)) == 0   # interleaved, disjoint
+    # nested kept sets (a smaller budget's set is inside a larger budget's): the overlap is the smaller size
+    sc = wl.random_scores(3, 1, 500)[0]
+    small, large = oracle.select_topk(sc, 8, 60), oracle.select_topk(sc, 8, 200)
+    assert oracle.index_overlap(small, large) == 60
+
+
+def test_mass_recall_closed_forms_and_exact_sums():
+    from fractions import Fraction
+    rng = np.random.default_rng(32)
+    P = 257
+    sc = rng.random(P).astype(np.float32) ** 4
+    every = np.arange(P + 8)                                # prefix and the 8 window positions behind it
+    assert oracle.mass_recall(sc, every) == 1.0             # everything kept: all of the mass
+    assert oracle.mass_recall(sc, np.arange(P, P + 8)) == 0.0   # window positions carry no score
+    assert oracle.mass_recall(np.zeros(9, np.float32), np.arange(4)) == 0.0
+    # uniform mass: the recall is the kept share of the prefix
+    assert abs(oracle.mass_recall(np.full(P, 0.25, np.float32), np.arange(0, 100)) - 100 / P) < 1e-15
+    # all mass on one token: 1 if it is kept, else 0
+    one = np.zeros(P, np.float32)
+    one[41] = 3.0
+    assert oracle.mass_recall(one, [3, 41, 200]) == 1.0 and oracle.mass_recall(one, [3, 40, 200]) == 0.0
+    # a set and its complement split the mass; exact rational arithmetic bounds the fp64 rounding
+    idx = np.sort(rng.choice(P, 60, replace=False))
+    rest = np.setdiff1d(np.arange(P), idx)
+    assert abs(oracle.mass_recall(sc, idx) + oracle.mass_recall(sc, rest) - 1.0) < 1e-14
+    exact = sum(Fraction(float(sc[j])) for j in idx) / sum(Fraction(float(x)) for x in sc)
+    assert abs(oracle.mass_recall(sc, idx) - float(exact)) < 1e-14
+    # the top-k set of a row has the largest recall of any set of its size (brute force, tiny row)
+    tiny = rng.random(9).astype(np.float32)
+    best = oracle.mass_recall(tiny, oracle.select_topk(tiny, 0, 4))
+    for comb in itertools.combinations(range(9), 4):
+        assert oracle.mass_recall(tiny, comb) <= best + 1e-15
+
+
 # ----------------------------------------------------------------------------- decode over the cache
 
 @pytest.mark.parametrize("layout", ["compact", "token_major"])
