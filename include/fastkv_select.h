@@ -159,6 +159,25 @@ enum { FKV_KV_COMPACT = 0, FKV_KV_TOKEN_MAJOR = 1 };
 int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,
                          int32_t kv_layout, const int32_t *n_per_seq, float *out, void *stream);
 
+/* Diagnostics of Sec. 3 on device-resident results.  Both run one block per row on `stream`.
+ *
+ * fkv_index_overlap: count_out[r] = number of indices A_r and B_r share, for n_rows pairs of ascending, duplicate-free int32
+ * index lists (Sec. 3.1: overlap of the critical-token sets of two layers; the overlap ratio is
+ * the count over the set size).  Row r of a starts at a + r*a_stride (elements), likewise b; a
+ * stride of 0 compares every row with the same list.  n_a, n_b >= 0.  count_out [n_rows] int32,
+ * device.  Unsorted input gives an undefined count (never an out-of-bounds access).
+ *
+ * fkv_mass_recall: recall_out[r] = sum of scores_r[j] over the kept j in [0, n_scores) divided by
+ * the sum of the whole row (Sec. 3.2: share of the attention mass a token subset covers); kept
+ * indices outside the row (the window positions of a kept set) are skipped, a row without mass
+ * gives 0.  scores row r at scores + r*row_stride (n_scores fp32), idx row r at idx + r*idx_stride
+ * (n_idx int32, duplicate-free).  Sums are accumulated in fp64 in a fixed order; recall_out
+ * [n_rows] fp32, device. */
+int fkv_index_overlap(fkv_ctx *ctx, const int32_t *a, int64_t a_stride, int32_t n_a, const int32_t *b,
+                      int64_t b_stride, int32_t n_b, int32_t n_rows, int32_t *count_out, void *stream);
+int fkv_mass_recall(fkv_ctx *ctx, const float *scores, int64_t row_stride, int32_t n_scores, const int32_t *idx,
+                    int64_t idx_stride, int32_t n_idx, int32_t n_rows, float *recall_out, void *stream);
+
 /* compress_kv(K, V, budget): one layer's selection of Algorithm 1 in one call: score once,
  * select budget_b tokens per KV head, gather K/V; and, when x != NULL, also the TSP leg
  * (HiddenCompress): select k_tsp_b tokens on the all-head score and gather hidden rows.

@@ -23,6 +23,7 @@ EXPORTS = [
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
+    "fkv_index_overlap", "fkv_mass_recall",
 ]
 
 
@@ -74,6 +75,8 @@ def load():
     lib.fkv_score_heads.argtypes = [vp, shp, vp, vp, vp, vp]
     lib.fkv_gather_kv_per_head.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
     lib.fkv_decode_attention.argtypes = [vp, shp, vp, vp, vp, i32, pi32, vp, vp]
+    lib.fkv_index_overlap.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
+    lib.fkv_mass_recall.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
     lib.fkv_count_from_rate.restype = i32
     lib.fkv_count_from_rate.argtypes = [i32, ctypes.c_double]
     lib.fkv_set_score_path.argtypes = [vp, ctypes.c_int]
@@ -290,6 +293,41 @@ class Context:
                                            _dev_ptr(k, "k", _BF16), _dev_ptr(v, "v", _BF16), lay, arr,
                                            _dev_ptr(out, "out", (torch.float32,)), _stream()), "fkv_decode_attention")
         return out
+
+    def fkv_index_overlap(self, a, b, count_out=None):
+        """a [R,n_a], b [R,n_b] (or [n_b]: one list for every row) ascending int32 -> shared-index counts [R] int32"""
+        a2 = a if a.dim() == 2 else a.unsqueeze(0)
+        rows = a2.shape[0]
+        b_stride = 0 if b.dim() == 1 else b.stride(0)
+        n_b = b.shape[-1]
+        if b.dim() == 2 and b.shape[0] != rows:
+            raise ValueError("a and b need the same number of rows")
+        if (a2.shape[1] > 0 and a2.stride(1) != 1) or (n_b > 0 and b.stride(-1) != 1):
+            raise ValueError("index rows must be contiguous")
+        if count_out is None:
+            count_out = torch.empty((rows,), dtype=torch.int32, device=a.device)
+        _check(load().fkv_index_overlap(self.handle, _dev_ptr(a2, "a", (torch.int32,), True), a2.stride(0) if rows > 1 else 0,
+                                        a2.shape[1], _dev_ptr(b, "b", (torch.int32,), True), b_stride, n_b, rows,
+                                        _dev_ptr(count_out, "count_out", (torch.int32,)), _stream()), "fkv_index_overlap")
+        return count_out
+
+    def fkv_mass_recall(self, scores, idx, recall_out=None):
+        """scores [R,P] fp32, idx [R,n] int32 -> share of each row's mass the kept indices cover, [R] fp32"""
+        s2 = scores if scores.dim() == 2 else scores.unsqueeze(0)
+        i2 = idx if idx.dim() == 2 else idx.unsqueeze(0)
+        rows = s2.shape[0]
+        if i2.shape[0] != rows:
+            raise ValueError("scores and idx need the same number of rows")
+        if (s2.shape[1] > 0 and s2.stride(1) != 1) or (i2.shape[1] > 0 and i2.stride(1) != 1):
+            raise ValueError("rows must be contiguous")
+        if recall_out is None:
+            recall_out = torch.empty((rows,), dtype=torch.float32, device=scores.device)
+        _check(load().fkv_mass_recall(self.handle, _dev_ptr(s2, "scores", (torch.float32,), True),
+                                      s2.stride(0) if rows > 1 else 0, s2.shape[1],
+                                      _dev_ptr(i2, "idx", (torch.int32,), True), i2.stride(0) if rows > 1 else 0,
+                                      i2.shape[1], rows, _dev_ptr(recall_out, "recall_out", (torch.float32,)),
+                                      _stream()), "fkv_mass_recall")
+        return recall_out
 
     def fkv_set_score_path(self, mode):
         """0 auto, 1 two-pass kernels, 2 single-pass resident-grid kernel."""

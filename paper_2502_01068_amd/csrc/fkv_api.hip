@@ -75,7 +75,7 @@ struct fkv_ctx {
 
 namespace {
 
-const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather", "k_score_fused", "k_decode"};
+const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather", "k_score_fused", "k_decode", "k_diag"};
 
 int hip_fail(hipError_t e) {
   g_last_hip_error = (int)e;
@@ -617,6 +617,34 @@ int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, co
   hipStream_t st = static_cast<hipStream_t>(stream);
   Timed t(ctx, st, KID_DECODE);
   const hipError_t e = launch_decode(a, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+
+int fkv_index_overlap(fkv_ctx *ctx, const int32_t *a, int64_t a_stride, int32_t n_a, const int32_t *b,
+                      int64_t b_stride, int32_t n_b, int32_t n_rows, int32_t *count_out, void *stream) {
+  if (n_rows < 0 || n_a < 0 || n_b < 0 || a_stride < 0 || b_stride < 0) return FKV_EINVAL;
+  if (!ctx) return FKV_ENULL;
+  if (n_rows == 0) return FKV_OK;
+  if (!count_out || (n_a > 0 && !a) || (n_b > 0 && !b)) return FKV_ENULL;
+  ctx->ev_prev = nullptr;
+  DiagOverlapArgs p{a, b, a_stride, b_stride, n_a, n_b, count_out};
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timed t(ctx, st, KID_DIAG);
+  const hipError_t e = launch_index_overlap(p, n_rows, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+
+int fkv_mass_recall(fkv_ctx *ctx, const float *scores, int64_t row_stride, int32_t n_scores, const int32_t *idx,
+                    int64_t idx_stride, int32_t n_idx, int32_t n_rows, float *recall_out, void *stream) {
+  if (n_rows < 0 || n_scores < 0 || n_idx < 0 || row_stride < 0 || idx_stride < 0) return FKV_EINVAL;
+  if (!ctx) return FKV_ENULL;
+  if (n_rows == 0) return FKV_OK;
+  if (!recall_out || (n_scores > 0 && !scores) || (n_idx > 0 && !idx)) return FKV_ENULL;
+  ctx->ev_prev = nullptr;
+  DiagRecallArgs p{scores, row_stride, n_scores, idx, idx_stride, n_idx, recall_out};
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timed t(ctx, st, KID_DIAG);
+  const hipError_t e = launch_mass_recall(p, n_rows, st);
   return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 

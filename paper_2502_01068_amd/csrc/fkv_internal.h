@@ -39,7 +39,7 @@ extern __device__ unsigned long long fkv_block_ticks[1024 * 4];
 #endif
 
 // Kernel ids for the per-kernel timing facility.
-enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_SCORE_FUSED, KID_DECODE, KID_COUNT };
+enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_SCORE_FUSED, KID_DECODE, KID_DIAG, KID_COUNT };
 
 // Sequence map passed by value in the kernel arguments: where each sequence's tokens
 // start and which block range of the launch works on it.
@@ -142,6 +142,25 @@ struct DecodeArgs {
 };
 int decode_max_splits(void);
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
+
+// ---- diagnostics ------------------------------------------------------------------------
+struct DiagOverlapArgs {
+  const int32_t *a, *b;   // row r at a + r*a_stride / b + r*b_stride, ascending and duplicate-free
+  int64_t a_stride, b_stride;
+  int n_a, n_b;
+  int32_t *count_out;     // [n_rows]
+};
+struct DiagRecallArgs {
+  const float *scores;    // row r at scores + r*row_stride, n_scores entries
+  int64_t row_stride;
+  int n_scores;
+  const int32_t *idx;     // row r at idx + r*idx_stride, n_idx entries
+  int64_t idx_stride;
+  int n_idx;
+  float *recall_out;      // [n_rows]
+};
+hipError_t launch_index_overlap(const DiagOverlapArgs &p, int n_rows, hipStream_t s);
+hipError_t launch_mass_recall(const DiagRecallArgs &p, int n_rows, hipStream_t s);
 
 // ---- gather -----------------------------------------------------------------------------
 struct GatherJob {

@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, name), name
     assert sorted(fk.EXPORTS) == declared
     assert lib.fkv_version() >= 100
-    assert lib.fkv_profile_kernels() == 7
+    assert lib.fkv_profile_kernels() == 8
     assert lib.fkv_strerror(fk.FKV_EALIGN).decode().startswith("device pointer")
 
 
@@ -125,6 +125,10 @@ def test_entry_points_validate_before_touching_the_context(lib):
                                p16, 8192, None, p16, p16, None) == fk.FKV_ENULL                   # half a TSP leg
     assert lib.fkv_compress_kv(None, ctypes.byref(s), p16, p16, p16, k, p16, p16, p16,
                                None, 0, None, None, None, None) == fk.FKV_ENULL                   # ctx
+    assert lib.fkv_index_overlap(None, p16, 4, -1, p16, 4, 4, 1, p16, None) == fk.FKV_EINVAL      # n_a < 0
+    assert lib.fkv_index_overlap(None, p16, 4, 4, p16, 4, 4, 1, p16, None) == fk.FKV_ENULL        # ctx
+    assert lib.fkv_mass_recall(None, p16, -8, 8, p16, 4, 4, 1, p16, None) == fk.FKV_EINVAL        # stride < 0
+    assert lib.fkv_mass_recall(None, p16, 8, 8, p16, 4, 4, 1, p16, None) == fk.FKV_ENULL          # ctx
     assert lib.fkv_destroy(None) == fk.FKV_ENULL
     assert lib.fkv_set_score_path(None, 0) == fk.FKV_ENULL and lib.fkv_query_error(None, None) == fk.FKV_ENULL
 

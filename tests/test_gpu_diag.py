@@ -1,0 +1,74 @@
+"""GPU parity of the Sec. 3 diagnostics (kept-set overlap, mass recall) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_01068_amd import binding as fk
+from paper_2502_01068_amd import workloads as wl
+from parity import dev_bf16
+
+pytestmark = pytest.mark.gpu
+RECALL_TOL = 2e-6  # fp64 sums on both sides; the GPU rounds the quotient to fp32 (half an ulp = 6e-8 relative)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = fk.Context(max_total_tokens=40000, max_seqs=4)
+    yield c
+    c.close()
+
+
+def _sets(rng, rows, n, hi):
+    return np.stack([np.sort(rng.choice(hi, n, replace=False)) for _ in range(rows)]).astype(np.int32)
+
+
+@pytest.mark.parametrize("rows,n_a,n_b,hi", [
+    (1, 0, 7, 50), (1, 9, 0, 50), (3, 1, 1, 2), (4, 512, 512, 3000), (2, 1025, 6554, 32760), (5, 2048, 300, 2500),
+    (1, 26214, 26214, 131064),
+])
+def test_index_overlap_parity(ctx, rows, n_a, n_b, hi):
+    print("case: overlap rows=%d n_a=%d n_b=%d hi=%d" % (rows, n_a, n_b, hi), flush=True)
+    rng = np.random.default_rng(rows * 1000 + n_a + n_b)
+    a, b = _sets(rng, rows, n_a, hi), _sets(rng, rows, n_b, hi)
+    got = ctx.fkv_index_overlap(torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()).cpu().numpy()
+    want = [oracle.index_overlap(a[r], b[r]) for r in range(rows)]
+    np.testing.assert_array_equal(got, want)
+    # one list against every row, and a set against itself
+    got1 = ctx.fkv_index_overlap(torch.from_numpy(a).cuda(), torch.from_numpy(b[0]).cuda()).cpu().numpy()
+    np.testing.assert_array_equal(got1, [oracle.index_overlap(a[r], b[0]) for r in range(rows)])
+    same = ctx.fkv_index_overlap(torch.from_numpy(a).cuda(), torch.from_numpy(a).cuda()).cpu().numpy()
+    np.testing.assert_array_equal(same, np.full(rows, n_a))
+
+
+@pytest.mark.parametrize("rows,P,n", [(1, 1, 1), (2, 63, 20), (9, 2040, 512), (3, 32760, 6554), (1, 131064, 512), (2, 100, 0)])
+def test_mass_recall_parity(ctx, rows, P, n):
+    print("case: recall rows=%d P=%d n=%d" % (rows, P, n), flush=True)
+    sc = wl.random_scores(7, rows, P)
+    rng = np.random.default_rng(P + n)
+    idx = np.stack([np.sort(rng.choice(P + 8, n, replace=False)) for _ in range(rows)]).astype(np.int32).reshape(rows, n)
+    got = ctx.fkv_mass_recall(torch.from_numpy(sc).cuda(), torch.from_numpy(idx).cuda()).cpu().numpy()
+    want = np.array([oracle.mass_recall(sc[r], idx[r]) for r in range(rows)])
+    assert np.abs(got - want).max() <= RECALL_TOL, (got, want)
+    # zero rows have no mass: recall 0, not NaN
+    z = ctx.fkv_mass_recall(torch.zeros((rows, P), device="cuda"), torch.from_numpy(idx).cuda()).cpu().numpy()
+    np.testing.assert_array_equal(z, np.zeros(rows, np.float32))
+
+
+def test_diagnostics_on_a_selection(ctx):
+    """Recall and overlap of the kept sets a scored layer produces (config-1 shape): the top-k set's
+    recall is at least the kept share of the prefix, nested budgets overlap completely."""
+    print("case: diagnostics on selection L=2048", flush=True)
+    L, W = 2048, 8
+    s = wl.make_sequence(11, L)
+    shape = fk.make_shape(L, pool_mode="avg")
+    sg, st = ctx.fkv_score_window(shape, dev_bf16(s["q_win"]), dev_bf16(s["k"]))
+    small = ctx.fkv_select_topk(shape, sg, 256)
+    large = ctx.fkv_select_topk(shape, sg, 512)
+    ov = ctx.fkv_index_overlap(small, large).cpu().numpy()
+    np.testing.assert_array_equal(ov, np.full(8, 256))
+    rec = ctx.fkv_mass_recall(sg, small).cpu().numpy()
+    sg_h, small_h = sg.cpu().numpy(), small.cpu().numpy()
+    want = np.array([oracle.mass_recall(sg_h[g], small_h[g]) for g in range(8)])
+    assert np.abs(rec - want).max() <= RECALL_TOL
+    assert (rec >= (256 - W) / (L - W)).all()
