@@ -182,6 +182,35 @@ def gather_kv_per_head(kv, idx_head):
     return out
 
 
+def gather_kv_paged(kv, idx_kv, block_table, pages):
+    """KVCompress into a paged cache (the paper's Limitations section names paged attention as the
+    serving layout the method has to fit): kv [L,Hkv,d], idx_kv [Hkv,b]; pages
+    [n_pages,page_size,Hkv,d]; block_table[p] = physical page of logical page p of this sequence.
+    The t-th kept row of KV head g lands in page block_table[t // page_size], slot t % page_size.
+    Returns the updated copy of `pages`; every other slot keeps its content."""
+    kv = np.ascontiguousarray(kv)
+    out = np.array(pages, copy=True)
+    n_pages, page_size, Hkv, d = out.shape
+    if kv.shape[1:] != (Hkv, d):
+        raise ValueError("shape mismatch")
+    for g in range(Hkv):
+        for t in range(idx_kv.shape[1]):
+            page = int(block_table[t // page_size])
+            if not 0 <= page < n_pages:
+                raise IndexError("block table entry out of range")
+            out[page, t % page_size, g] = kv[int(idx_kv[g, t]), g]
+    return out
+
+
+def paged_view(pages, block_table, n):
+    """The first n logical tokens of a sequence in a paged cache, token-major [n,Hkv,d]."""
+    page_size = pages.shape[1]
+    out = np.empty((n,) + pages.shape[2:], dtype=pages.dtype)
+    for t in range(n):
+        out[t] = pages[int(block_table[t // page_size]), t % page_size]
+    return out
+
+
 def decode_attention(q, k, v, layout="compact", scale=None, precision="f32"):
     """Attention output of one new query token over a KV cache (the decoding step that reads the
     compressed cache, Algorithm 1 / Sec. 5.3).  q [Hq,d]; layout "compact": k, v [Hkv,n,d] (what

@@ -332,6 +332,42 @@ def test_compress_kv_composition_and_heavy_recall():
     assert recall > 0.8
 
 
+# ----------------------------------------------------------------------------- paged cache layout
+
+def test_paged_gather_round_trip_and_decode_equivalence():
+    rng = np.random.default_rng(41)
+    L, Hkv, d, b, ps, n_pages = 90, 2, 16, 37, 8, 11
+    kv = _rand_bf16(rng, (L, Hkv, d))
+    vv = _rand_bf16(rng, (L, Hkv, d))
+    idx = np.stack([np.sort(rng.choice(L, b, replace=False)) for _ in range(Hkv)]).astype(np.int32)
+    table = rng.permutation(n_pages)[:(b + ps - 1) // ps].astype(np.int32)      # 5 scattered pages
+    before = _rand_bf16(rng, (n_pages, ps, Hkv, d))
+    pages = oracle.gather_kv_paged(kv, idx, table, before)
+    # reading the pages back in logical order gives the compact gather (library index ops)
+    view = oracle.paged_view(pages, table, b)
+    compact = oracle.gather_kv(kv, idx)
+    np.testing.assert_array_equal(view.transpose(1, 0, 2), compact)
+    for g in range(Hkv):
+        np.testing.assert_array_equal(view[:, g], kv[idx[g], g])
+    # nothing else is touched: unused pages and the unused tail of the last page keep their content
+    touched = np.zeros((n_pages, ps), bool)
+    for t in range(b):
+        touched[table[t // ps], t % ps] = True
+    assert touched.sum() == b
+    np.testing.assert_array_equal(pages[~touched], before[~touched])
+    # an identity block table over a fresh pool is the token-major compact cache itself
+    ident = oracle.gather_kv_paged(kv, idx, np.arange(5), np.zeros((5, ps, Hkv, d), np.uint16))
+    np.testing.assert_array_equal(ident.reshape(5 * ps, Hkv, d)[:b].transpose(1, 0, 2), compact)
+    # decoding over the paged view equals decoding over the compact cache, bit for bit
+    vpages = oracle.gather_kv_paged(vv, idx, table, before)
+    q = _rand_bf16(rng, (4, d))
+    a = oracle.decode_attention(q, view, oracle.paged_view(vpages, table, b), "token_major")
+    c = oracle.decode_attention(q, compact, oracle.gather_kv(vv, idx), "compact")
+    np.testing.assert_array_equal(a, c)
+    with pytest.raises(IndexError):
+        oracle.gather_kv_paged(kv, idx, np.full(5, n_pages), before)
+
+
 # ----------------------------------------------------------------------------- diagnostics (Sec. 3)
 
 def test_index_overlap_matches_library_and_sets():
