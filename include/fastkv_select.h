@@ -159,6 +159,25 @@ enum { FKV_KV_COMPACT = 0, FKV_KV_TOKEN_MAJOR = 1 };
 int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,
                          int32_t kv_layout, const int32_t *n_per_seq, float *out, void *stream);
 
+/* Paged cache layout (the serving layout the paper's Limitations section says the method has to
+ * fit): a pool of pages [n_pages][page_size][Hkv][d] bf16 per tensor and a DEVICE block table
+ * [B][max_pages_per_seq] int32; logical token t of sequence b lives in page
+ * block_table[b][t / page_size], slot t % page_size.  page_size is a power of two;
+ * n_pages * page_size * Hkv < 2^31; max_pages_per_seq * page_size covers every sequence's count.
+ *
+ * fkv_gather_kv_paged: KVCompress straight into the pages: the t-th kept row of KV head g of
+ * sequence b (idx_kv as in fkv_gather_kv) goes to logical token t.  Other slots are not written; a
+ * table entry outside [0, n_pages) writes nothing.  v / v_pages may both be NULL.
+ *
+ * fkv_decode_attention_paged: fkv_decode_attention over the first n_per_seq[b] logical tokens of
+ * each sequence.  A table entry outside the pool is clamped into it (wrong result, no fault). */
+int fkv_gather_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const void *v, const int32_t *idx_kv,
+                        const int32_t *budget_per_seq, const int32_t *block_table, int32_t max_pages_per_seq,
+                        int32_t page_size, int64_t n_pages, void *k_pages, void *v_pages, void *stream);
+int fkv_decode_attention_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k_pages,
+                               const void *v_pages, const int32_t *block_table, int32_t max_pages_per_seq,
+                               int32_t page_size, int64_t n_pages, const int32_t *n_per_seq, float *out, void *stream);
+
 /* Diagnostics of Sec. 3 on device-resident results.  Both run one block per row on `stream`.
  *
  * fkv_index_overlap: count_out[r] = number of indices A_r and B_r share, for n_rows pairs of ascending, duplicate-free int32

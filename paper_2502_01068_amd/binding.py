@@ -23,7 +23,7 @@ EXPORTS = [
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
-    "fkv_index_overlap", "fkv_mass_recall",
+    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged",
 ]
 
 
@@ -75,6 +75,8 @@ def load():
     lib.fkv_score_heads.argtypes = [vp, shp, vp, vp, vp, vp]
     lib.fkv_gather_kv_per_head.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
     lib.fkv_decode_attention.argtypes = [vp, shp, vp, vp, vp, i32, pi32, vp, vp]
+    lib.fkv_gather_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp]
+    lib.fkv_decode_attention_paged.argtypes = [vp, shp, vp, vp, vp, vp, i32, i32, i64, pi32, vp, vp]
     lib.fkv_index_overlap.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
     lib.fkv_mass_recall.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
     lib.fkv_count_from_rate.restype = i32
@@ -292,6 +294,31 @@ class Context:
         _check(load().fkv_decode_attention(self.handle, ctypes.byref(shape), _dev_ptr(q, "q", _BF16),
                                            _dev_ptr(k, "k", _BF16), _dev_ptr(v, "v", _BF16), lay, arr,
                                            _dev_ptr(out, "out", (torch.float32,)), _stream()), "fkv_decode_attention")
+        return out
+
+    def fkv_gather_kv_paged(self, shape, k, v, idx_kv, budget_per_seq, block_table, k_pages, v_pages=None):
+        """k, v [sum L,Hkv,d]; idx_kv [Hkv,sum budget]; block_table [B,max_pages] int32 (GPU);
+        k_pages, v_pages [n_pages,page_size,Hkv,d] are updated in place"""
+        counts, arr = _counts(shape, budget_per_seq)
+        _check(load().fkv_gather_kv_paged(self.handle, ctypes.byref(shape), _dev_ptr(k, "k", _BF16),
+                                          _dev_ptr(v, "v", _BF16, True), _dev_ptr(idx_kv, "idx_kv", (torch.int32,)), arr,
+                                          _dev_ptr(block_table, "block_table", (torch.int32,)), block_table.shape[-1],
+                                          k_pages.shape[1], k_pages.shape[0], _dev_ptr(k_pages, "k_pages", _BF16),
+                                          _dev_ptr(v_pages, "v_pages", _BF16, True), _stream()), "fkv_gather_kv_paged")
+        return k_pages, v_pages
+
+    def fkv_decode_attention_paged(self, shape, q, k_pages, v_pages, block_table, n_per_seq, out=None):
+        """q [B,Hq,d] bf16; k_pages, v_pages [n_pages,page_size,Hkv,d]; block_table [B,max_pages] -> out [B,Hq,d] fp32"""
+        counts = [int(c) for c in ([n_per_seq] * shape.n_seq if isinstance(n_per_seq, int) else n_per_seq)]
+        arr = _i32_array(counts)
+        if out is None:
+            out = torch.empty((shape.n_seq, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device=q.device)
+        _check(load().fkv_decode_attention_paged(self.handle, ctypes.byref(shape), _dev_ptr(q, "q", _BF16),
+                                                 _dev_ptr(k_pages, "k_pages", _BF16), _dev_ptr(v_pages, "v_pages", _BF16),
+                                                 _dev_ptr(block_table, "block_table", (torch.int32,)), block_table.shape[-1],
+                                                 k_pages.shape[1], k_pages.shape[0], arr,
+                                                 _dev_ptr(out, "out", (torch.float32,)), _stream()),
+               "fkv_decode_attention_paged")
         return out
 
     def fkv_index_overlap(self, a, b, count_out=None):

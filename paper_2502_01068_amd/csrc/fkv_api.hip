@@ -578,19 +578,44 @@ int32_t fkv_count_from_rate(int32_t n_tokens, double rate) {
   return (int32_t)x;
 }
 
-int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,
-                         int32_t kv_layout, const int32_t *n_per_seq, float *out, void *stream) {
+namespace {
+struct Paging {  // block-table addressing of a paged cache; table == nullptr: none
+  const int32_t *table;
+  int max_pages, page_size;
+  int64_t n_pages;
+};
+int page_shift_of(int page_size) {  // log2 of a power of two, else -1
+  if (page_size < 1 || (page_size & (page_size - 1)) != 0) return -1;
+  int sh = 0;
+  while ((1 << sh) < page_size) ++sh;
+  return sh;
+}
+int check_paging(const Paging &pg, int Hkv) {
+  if (!pg.table) return FKV_ENULL;
+  if (page_shift_of(pg.page_size) < 0 || pg.max_pages < 1 || pg.n_pages < 1) return FKV_EINVAL;
+  if (pg.n_pages * pg.page_size > INT32_MAX / Hkv) return FKV_EINVAL;  // slot * Hkv stays below 2^31
+  return FKV_OK;
+}
+
+int decode_common(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,
+                  int32_t kv_layout, const Paging *pg, const int32_t *n_per_seq, float *out, void *stream) {
   Resolved r;
   int rc = resolve(shape, &r);
   if (rc != FKV_OK) return rc;
   if (!q || !k || !v || !n_per_seq || !out) return FKV_ENULL;
-  if (kv_layout != FKV_KV_COMPACT && kv_layout != FKV_KV_TOKEN_MAJOR) return FKV_EINVAL;
+  if (pg) {
+    rc = check_paging(*pg, r.Hkv);
+    if (rc != FKV_OK) return rc;
+  } else if (kv_layout != FKV_KV_COMPACT && kv_layout != FKV_KV_TOKEN_MAJOR) {
+    return FKV_EINVAL;
+  }
   DecodeArgs a{};
   int64_t tot = 0;
   int n_max = 0;
   a.off[0] = 0;
   for (int b = 0; b < r.n_seq; ++b) {
     if (n_per_seq[b] < 1) return FKV_EINVAL;
+    if (pg && n_per_seq[b] > (int64_t)pg->max_pages * pg->page_size) return FKV_EINVAL;
     tot += n_per_seq[b];
     if (tot > INT32_MAX) return FKV_EINVAL;
     a.off[b + 1] = (int)tot;
@@ -605,8 +630,15 @@ int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, co
   a.v = static_cast<const uint16_t *>(v);
   a.out = out;
   a.part = reinterpret_cast<float *>(ctx->ws + ctx->lay.dec_part);
-  a.tok_stride = kv_layout == FKV_KV_COMPACT ? kHeadDim : (int64_t)r.Hkv * kHeadDim;
-  a.head_stride = kv_layout == FKV_KV_COMPACT ? tot * kHeadDim : kHeadDim;
+  const bool token_major = pg || kv_layout == FKV_KV_TOKEN_MAJOR;
+  a.tok_stride = token_major ? (int64_t)r.Hkv * kHeadDim : kHeadDim;
+  a.head_stride = token_major ? kHeadDim : tot * kHeadDim;
+  if (pg) {
+    a.block_table = pg->table;
+    a.max_pages = pg->max_pages;
+    a.page_shift = page_shift_of(pg->page_size);
+    a.n_pages = (int)pg->n_pages;
+  }
   a.Hq = r.Hq; a.Hkv = r.Hkv; a.G = r.G; a.n_seq = r.n_seq;
   int splits = (n_max + 63) / 64;  // at least 64 tokens per block, at most decode_max_splits() blocks per head
   if (splits < 1) splits = 1;
@@ -617,6 +649,58 @@ int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, co
   hipStream_t st = static_cast<hipStream_t>(stream);
   Timed t(ctx, st, KID_DECODE);
   const hipError_t e = launch_decode(a, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+}  // namespace
+
+int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,
+                         int32_t kv_layout, const int32_t *n_per_seq, float *out, void *stream) {
+  return decode_common(ctx, shape, q, k, v, kv_layout, nullptr, n_per_seq, out, stream);
+}
+
+int fkv_decode_attention_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k_pages,
+                               const void *v_pages, const int32_t *block_table, int32_t max_pages_per_seq,
+                               int32_t page_size, int64_t n_pages, const int32_t *n_per_seq, float *out, void *stream) {
+  const Paging pg{block_table, max_pages_per_seq, page_size, n_pages};
+  return decode_common(ctx, shape, q, k_pages, v_pages, FKV_KV_TOKEN_MAJOR, &pg, n_per_seq, out, stream);
+}
+
+int fkv_gather_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const void *v, const int32_t *idx_kv,
+                        const int32_t *budget_per_seq, const int32_t *block_table, int32_t max_pages_per_seq,
+                        int32_t page_size, int64_t n_pages, void *k_pages, void *v_pages, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!k || !idx_kv || !k_pages) return FKV_ENULL;
+  if ((v == nullptr) != (v_pages == nullptr)) return FKV_ENULL;
+  PagedGatherArgs g{};
+  rc = check_counts(r, budget_per_seq, g.cnt_off);
+  if (rc != FKV_OK) return rc;
+  const Paging pg{block_table, max_pages_per_seq, page_size, n_pages};
+  rc = check_paging(pg, r.Hkv);
+  if (rc != FKV_OK) return rc;
+  for (int b = 0; b < r.n_seq; ++b)
+    if (budget_per_seq[b] > (int64_t)max_pages_per_seq * page_size) return FKV_EINVAL;
+  if ((int64_t)g.cnt_off[r.n_seq] * r.Hkv > (INT32_MAX >> 5)) return FKV_EINVAL;  // 16-byte chunk ids stay below 2^31
+  if (misaligned(k) || misaligned(v) || misaligned(k_pages) || misaligned(v_pages)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  g.src[0] = static_cast<const uint8_t *>(k);
+  g.src[1] = static_cast<const uint8_t *>(v);
+  g.pages[0] = static_cast<uint8_t *>(k_pages);
+  g.pages[1] = static_cast<uint8_t *>(v_pages);
+  g.idx = idx_kv;
+  g.block_table = block_table;
+  g.max_pages = max_pages_per_seq;
+  g.page_shift = page_shift_of(page_size);
+  g.n_pages = (int)n_pages;
+  g.Hkv = r.Hkv;
+  g.total_rows = g.cnt_off[r.n_seq];
+  g.n_seq = r.n_seq;
+  for (int b = 0; b <= r.n_seq; ++b) g.cu[b] = r.cu[b];
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timed t(ctx, st, KID_GATHER);
+  const hipError_t e = launch_gather_paged(g, st);
   return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 

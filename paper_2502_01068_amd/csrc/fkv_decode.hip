@@ -49,6 +49,7 @@ __device__ __forceinline__ void dec_merge(DecState &a, float m2, float l2, const
 }
 
 // grid (n_split, Hkv, B); partial results part[((b*Hq + h)*n_split + s)*(128+2)]: 128 weighted sums, max, sum
+template <bool kPaged>
 __global__ __launch_bounds__(kDecThreads) void k_decode_partial(DecodeArgs a) {
   __shared__ float lds[kDecWaves][kMaxGroup][16][10];
   const int s = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
@@ -78,15 +79,21 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_partial(DecodeArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) st[hl].acc[i] = 0.f;
   }
-  const uint16_t *kb = a.k + (size_t)g * a.head_stride + (size_t)a.off[b] * a.tok_stride + c * 8;
-  const uint16_t *vb = a.v + (size_t)g * a.head_stride + (size_t)a.off[b] * a.tok_stride + c * 8;
+  const size_t first = kPaged ? 0 : (size_t)a.off[b];  // a paged sequence is addressed through its block table
+  const uint16_t *kb = a.k + (size_t)g * a.head_stride + first * a.tok_stride + c * 8;
+  const uint16_t *vb = a.v + (size_t)g * a.head_stride + first * a.tok_stride + c * 8;
+  const int32_t *table = kPaged ? a.block_table + (size_t)b * a.max_pages : nullptr;
 
   constexpr int kU = 4;  // token steps whose loads are in flight together
   for (int tb = t0 + wave * 4; tb < t1; tb += kDecWaves * 4 * kU) {  // uniform per wave
     u32x4 kw[kU], vw[kU];
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
-      const int t = min(tb + u * kDecWaves * 4 + tq, t1 - 1);
+      int t = min(tb + u * kDecWaves * 4 + tq, t1 - 1);
+      if (kPaged) {  // physical slot; an entry outside the pool is clamped into it (never out of bounds)
+        const int page = min(max(table[t >> a.page_shift], 0), a.n_pages - 1);
+        t = (page << a.page_shift) + (t & ((1 << a.page_shift) - 1));
+      }
       kw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kb + (size_t)t * a.tok_stride));
       vw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vb + (size_t)t * a.tok_stride));
     }
@@ -208,7 +215,10 @@ __global__ __launch_bounds__(4 * kHeadDim) void k_decode_combine(DecodeArgs a) {
 }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s) {
-  hipLaunchKernelGGL(k_decode_partial, dim3(a.n_split, a.Hkv, a.n_seq), dim3(kDecThreads), 0, s, a);
+  if (a.block_table)
+    hipLaunchKernelGGL(k_decode_partial<true>, dim3(a.n_split, a.Hkv, a.n_seq), dim3(kDecThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(k_decode_partial<false>, dim3(a.n_split, a.Hkv, a.n_seq), dim3(kDecThreads), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_decode_combine, dim3(a.Hq, a.n_seq), dim3(4 * kHeadDim), 0, s, a);

@@ -70,6 +70,51 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(GatherArgs a) {
 #endif
 }
 
+// Paged destination: chunk c of the launch is 16 bytes of (kept slot t, KV head g), heads fastest,
+// so the 16*Hkv lanes of one slot write one contiguous [Hkv][d] page entry.  blockIdx.y picks K or V.
+// A block-table entry outside [0, n_pages) writes nothing.
+__global__ __launch_bounds__(kGatherThreads) void k_gather_paged(PagedGatherArgs a) {
+  const int which = blockIdx.y;
+  const uint8_t *src = a.src[which];
+  uint8_t *pages = a.pages[which];
+  constexpr uint32_t kCpr = kHeadDim * 2 / 16;  // 16 chunks per head row
+  const uint32_t n_chunks = (uint32_t)a.total_rows * a.Hkv * kCpr;
+  const uint32_t c0 = blockIdx.x * (kGatherUnroll * kGatherThreads) + threadIdx.x;
+  u32x4 val[kGatherUnroll];
+  u32x4 *dst[kGatherUnroll];
+#pragma unroll
+  for (int u = 0; u < kGatherUnroll; ++u) {
+    const uint32_t c = c0 + u * kGatherThreads;
+    dst[u] = nullptr;
+    if (c < n_chunks) {
+      const uint32_t col = c & (kCpr - 1u), r = c / kCpr;
+      const uint32_t t = r / (uint32_t)a.Hkv, g = r - t * a.Hkv;
+      int b = 0;
+      while (b + 1 < a.n_seq && (int)t >= a.cnt_off[b + 1]) ++b;
+      const uint32_t tl = t - a.cnt_off[b];
+      const int page = a.block_table[(size_t)b * a.max_pages + (tl >> a.page_shift)];
+      const size_t tok = (size_t)a.cu[b] + (size_t)a.idx[(size_t)g * a.total_rows + t];
+      val[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (tok * a.Hkv + g) * (kHeadDim * 2)) + col);
+      if (page >= 0 && page < a.n_pages) {
+        const size_t slot = ((size_t)page << a.page_shift) + (tl & ((1u << a.page_shift) - 1u));
+        dst[u] = reinterpret_cast<u32x4 *>(pages + (slot * a.Hkv + g) * (kHeadDim * 2)) + col;
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kGatherUnroll; ++u)
+    if (dst[u]) __builtin_nontemporal_store(val[u], dst[u]);
+}
+
+hipError_t launch_gather_paged(const PagedGatherArgs &a, hipStream_t s) {
+  const int64_t chunks = (int64_t)a.total_rows * a.Hkv * (kHeadDim * 2 / 16);
+  const int64_t per_block = (int64_t)kGatherThreads * kGatherUnroll;
+  const int n_blocks = (int)((chunks + per_block - 1) / per_block);
+  if (n_blocks <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_gather_paged, dim3(n_blocks, a.src[1] ? 2 : 1), dim3(kGatherThreads), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_gather(const GatherArgs &a, int n_blocks, hipStream_t s) {
   if (n_blocks <= 0) return hipSuccess;
   hipLaunchKernelGGL(k_gather, dim3(n_blocks), dim3(kGatherThreads), 0, s, a);

@@ -139,6 +139,10 @@ struct DecodeArgs {
   int Hq, Hkv, G, n_split, n_seq;
   float scale_log2e;
   int off[FKV_MAX_SEQS + 1];
+  // paged cache (block_table != nullptr): k, v are page pools [n_pages][page_size][Hkv][d]; logical
+  // token t of sequence b lives in page block_table[b*max_pages + t/page_size], slot t % page_size
+  const int32_t *block_table;
+  int max_pages, page_shift, n_pages;
 };
 int decode_max_splits(void);
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
@@ -183,6 +187,18 @@ struct GatherArgs {
   int n_seq;
   int cu[FKV_MAX_SEQS + 1];
 };
+// KVCompress straight into a paged cache [n_pages][page_size][Hkv][d] through a block table.
+struct PagedGatherArgs {
+  const uint8_t *src[2];        // K, V: [sum L][Hkv][d] bf16 (V may be nullptr)
+  uint8_t *pages[2];            // K, V page pools
+  const int32_t *idx;           // [Hkv][total_rows]
+  const int32_t *block_table;   // [n_seq][max_pages]
+  int max_pages, page_shift, n_pages;
+  int Hkv, total_rows, n_seq;
+  int cu[FKV_MAX_SEQS + 1];
+  int cnt_off[FKV_MAX_SEQS + 1];
+};
+hipError_t launch_gather_paged(const PagedGatherArgs &a, hipStream_t s);
 int gather_blocks_per_head(const GatherJob &j);
 hipError_t launch_gather(const GatherArgs &a, int n_blocks, hipStream_t s);
 

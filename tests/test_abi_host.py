@@ -129,6 +129,14 @@ def test_entry_points_validate_before_touching_the_context(lib):
     assert lib.fkv_index_overlap(None, p16, 4, 4, p16, 4, 4, 1, p16, None) == fk.FKV_ENULL        # ctx
     assert lib.fkv_mass_recall(None, p16, -8, 8, p16, 4, 4, 1, p16, None) == fk.FKV_EINVAL        # stride < 0
     assert lib.fkv_mass_recall(None, p16, 8, 8, p16, 4, 4, 1, p16, None) == fk.FKV_ENULL          # ctx
+    n1 = (ctypes.c_int32 * 1)(300)
+    assert lib.fkv_gather_kv_paged(None, ctypes.byref(s), p16, p16, p16, k, p16, 8, 48, 100, p16, p16, None) == fk.FKV_EINVAL  # page size
+    assert lib.fkv_gather_kv_paged(None, ctypes.byref(s), p16, p16, p16, k, p16, 8, 32, 100, p16, p16, None) == fk.FKV_EINVAL  # 8*32 < 512
+    assert lib.fkv_gather_kv_paged(None, ctypes.byref(s), p16, p16, p16, k, None, 8, 64, 100, p16, p16, None) == fk.FKV_ENULL  # table
+    assert lib.fkv_gather_kv_paged(None, ctypes.byref(s), p16, p16, p16, k, p16, 8, 64, 100, p16, p16, None) == fk.FKV_ENULL   # ctx
+    assert lib.fkv_decode_attention_paged(None, ctypes.byref(s), p16, p16, p16, p16, 4, 64, 100, n1, p16, None) == fk.FKV_EINVAL  # 4*64 < 300
+    assert lib.fkv_decode_attention_paged(None, ctypes.byref(s), p16, p16, p16, p16, 8, 64, 0, n1, p16, None) == fk.FKV_EINVAL   # no pages
+    assert lib.fkv_decode_attention_paged(None, ctypes.byref(s), p16, p16, p16, p16, 8, 64, 100, n1, p16, None) == fk.FKV_ENULL  # ctx
     assert lib.fkv_destroy(None) == fk.FKV_ENULL
     assert lib.fkv_set_score_path(None, 0) == fk.FKV_ENULL and lib.fkv_query_error(None, None) == fk.FKV_ENULL
 
