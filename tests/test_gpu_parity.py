@@ -136,6 +136,30 @@ def test_select_bit_exact(ctx, P, ks, ties):
             np.testing.assert_array_equal(idx[r], oracle.select_topk(scores[r], W, k), err_msg="row %d k %d" % (r, k))
 
 
+@pytest.mark.parametrize("P,rows,ks", [
+    (1000003, 2, [8, 4096, 200001]),     # 123 slices of the multi-block chain
+    (40000, 66, [8008]),                 # more row instances than the chain's state holds: one-block chunked kernel
+    (32766, 1, [6554]), (32767, 2, [6554]),  # either side of the register-resident limit
+])
+def test_select_long_rows(P, rows, ks):
+    W = 8
+    print("case: select long rows P=%d rows=%d ks=%s" % (P, rows, ks), flush=True)
+    scores = wl.random_scores(P % 1000, rows, P, ties=0.25)
+    scores[rows - 1, : P // 2] = np.float32(0.5)   # half the last row tied above most of the rest
+    c = fk.Context(max_total_tokens=P + W, max_seqs=1)
+    try:
+        d = torch.from_numpy(scores).cuda()
+        shape = fk.make_shape(P + W)
+        for k in ks:
+            idx = c.fkv_select_topk(shape, d, k).cpu().numpy()
+            for r in sorted({0, rows // 2, rows - 1}):
+                np.testing.assert_array_equal(idx[r], oracle.select_topk(scores[r], W, k), err_msg="row %d k %d" % (r, k))
+            for r in range(rows):  # structure of every row: ascending, unique, window at the end
+                assert (np.diff(idx[r]) > 0).all() and idx[r, -W:].tolist() == list(range(P, P + W))
+    finally:
+        c.close()
+
+
 def test_select_negative_and_zero_scores(ctx):
     # the API takes any non-NaN fp32: order must hold across sign; -0.0 and +0.0 tie (lower index wins)
     print("case: select signed scores", flush=True)
