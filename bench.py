@@ -314,7 +314,24 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     copy_gbs = 2 * big.numel() * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del big, dst
+    del dst
+    # read-only bandwidth with the K stream's access pattern, 16 launches over 16 different 256 MiB regions
+    # (cold in every cache), plain and non-temporal loads
+    pool = torch.empty(1 << 32, dtype=torch.uint8, device="cuda")
+    pool.view(torch.int32).fill_(0x3F803F80)
+    read_gbs = {}
+    for name, streaming in (("plain", False), ("nontemporal", True)):
+        regions = [pool[i << 28:(i + 1) << 28] for i in range(16)]
+        for r in regions[:4]:
+            ctx.fkv_probe_read(r, streaming)
+        torch.cuda.synchronize()
+        e0.record()
+        for r in regions:
+            ctx.fkv_probe_read(r, streaming)
+        e1.record()
+        torch.cuda.synchronize()
+        read_gbs[name] = pool.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del pool, regions, big
 
     total_bytes = wl.algorithmic_bytes(L, k_tsp, budget)
     tokens_per_s = L / (wall_ms * 1e-3)
@@ -341,7 +358,7 @@ def main():
                  "frac_of_peak": total_bytes / (wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                  "device_ms_per_step": dev_ms, "warm_ms_per_step": warm_wall_ms, "warm_device_ms": warm_dev_ms,
                  "per_kernel_us": per_kernel_us, "event_record_cost_us": event_cost_us,
-                 "measured_copy_GBps": copy_gbs,
+                 "measured_copy_GBps": copy_gbs, "measured_read_GBps": read_gbs,
                  "frac_of_measured_copy": total_bytes / (wall_ms * 1e-3) / 1e9 / copy_gbs,
                  "two_calls_in_flight": None if two_ms is None else {
                      "ms_per_step": two_ms, "tokens_per_s": L / (two_ms * 1e-3),

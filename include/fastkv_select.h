@@ -178,6 +178,13 @@ int fkv_decode_attention_paged(fkv_ctx *ctx, const fkv_shape *shape, const void 
                                const void *v_pages, const int32_t *block_table, int32_t max_pages_per_seq,
                                int32_t page_size, int64_t n_pages, const int32_t *n_per_seq, float *out, void *stream);
 
+/* Measurement aid for callers that want the machine's achievable read bandwidth next to their
+ * timings: one launch that only reads `bytes` (a multiple of 65536) of device memory at `src` with
+ * the access pattern of the score kernels' K stream; streaming != 0 uses non-temporal loads.
+ * Nothing is written.  Time it with events on `stream` or through fkv_profile_read
+ * ("k_probe_read"). */
+int fkv_probe_read(fkv_ctx *ctx, const void *src, int64_t bytes, int32_t streaming, void *stream);
+
 /* Diagnostics of Sec. 3 on device-resident results.  Both run one block per row on `stream`.
  *
  * fkv_index_overlap: count_out[r] = number of indices A_r and B_r share, for n_rows pairs of ascending, duplicate-free int32

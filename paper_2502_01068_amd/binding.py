@@ -23,7 +23,7 @@ EXPORTS = [
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
-    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged",
+    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read",
 ]
 
 
@@ -77,6 +77,7 @@ def load():
     lib.fkv_decode_attention.argtypes = [vp, shp, vp, vp, vp, i32, pi32, vp, vp]
     lib.fkv_gather_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp]
     lib.fkv_decode_attention_paged.argtypes = [vp, shp, vp, vp, vp, vp, i32, i32, i64, pi32, vp, vp]
+    lib.fkv_probe_read.argtypes = [vp, vp, i64, i32, vp]
     lib.fkv_index_overlap.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
     lib.fkv_mass_recall.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
     lib.fkv_count_from_rate.restype = i32
@@ -320,6 +321,11 @@ class Context:
                                                  _dev_ptr(out, "out", (torch.float32,)), _stream()),
                "fkv_decode_attention_paged")
         return out
+
+    def fkv_probe_read(self, src, streaming=False):
+        """Read-only launch over the tensor's bytes (size must be a multiple of 64 KiB)."""
+        _check(load().fkv_probe_read(self.handle, _dev_ptr(src, "src"), src.numel() * src.element_size(),
+                                     1 if streaming else 0, _stream()), "fkv_probe_read")
 
     def fkv_index_overlap(self, a, b, count_out=None):
         """a [R,n_a], b [R,n_b] (or [n_b]: one list for every row) ascending int32 -> shared-index counts [R] int32"""

@@ -75,7 +75,7 @@ struct fkv_ctx {
 
 namespace {
 
-const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather", "k_score_fused", "k_decode", "k_diag"};
+const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather", "k_score_fused", "k_decode", "k_diag", "k_probe_read"};
 
 int hip_fail(hipError_t e) {
   g_last_hip_error = (int)e;
@@ -701,6 +701,19 @@ int fkv_gather_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *k, con
   hipStream_t st = static_cast<hipStream_t>(stream);
   Timed t(ctx, st, KID_GATHER);
   const hipError_t e = launch_gather_paged(g, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+
+int fkv_probe_read(fkv_ctx *ctx, const void *src, int64_t bytes, int32_t streaming, void *stream) {
+  if (bytes < 0 || (bytes & 65535) != 0 || bytes / 65536 > INT32_MAX) return FKV_EINVAL;
+  if (!src && bytes > 0) return FKV_ENULL;
+  if (misaligned(src)) return FKV_EALIGN;
+  if (!ctx) return FKV_ENULL;
+  ctx->ev_prev = nullptr;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timed t(ctx, st, KID_PROBE);
+  const hipError_t e = launch_probe_read(src, bytes, streaming != 0, ctx->n_cu > 0 ? ctx->n_cu : 256,
+                                         reinterpret_cast<uint32_t *>(ctx->ws), st);
   return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 

@@ -39,7 +39,7 @@ extern __device__ unsigned long long fkv_block_ticks[1024 * 4];
 #endif
 
 // Kernel ids for the per-kernel timing facility.
-enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_SCORE_FUSED, KID_DECODE, KID_DIAG, KID_COUNT };
+enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_SCORE_FUSED, KID_DECODE, KID_DIAG, KID_PROBE, KID_COUNT };
 
 // Sequence map passed by value in the kernel arguments: where each sequence's tokens
 // start and which block range of the launch works on it.
@@ -165,6 +165,9 @@ struct DiagRecallArgs {
 };
 hipError_t launch_index_overlap(const DiagOverlapArgs &p, int n_rows, hipStream_t s);
 hipError_t launch_mass_recall(const DiagRecallArgs &p, int n_rows, hipStream_t s);
+
+// ---- read-bandwidth probe -----------------------------------------------------------------
+hipError_t launch_probe_read(const void *src, int64_t bytes, bool streaming, int n_blocks, uint32_t *sink, hipStream_t s);
 
 // ---- gather -----------------------------------------------------------------------------
 struct GatherJob {

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kThreads) void k_stats(ScoreArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) { mx[r] = kNegBig; sm[r] = 0.f; }
 
-    stream_head(a, qa, tok_base, Lb, g, t0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
+    stream_head<true>(a, qa, tok_base, Lb, g, t0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
       const int tok = t0 + st * kSub + n;
       const bool valid = tok < t1;
 #pragma unroll
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
 #pragma unroll
     for (int q = 0; q < 16; ++q) cst[q] = rs[(q >> 2) * 8 + hi * 4 + (q & 3)];
 
-    stream_head(a, qa, tok_base, Lb, g, j0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
+    stream_head<true>(a, qa, tok_base, Lb, g, j0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
       const int tok = j0 + st * kSub + n;
       const bool inb = tok >= 0 && tok < P;  // only prefix tokens are scored
 #pragma unroll

@@ -72,3 +72,14 @@ def test_diagnostics_on_a_selection(ctx):
     want = np.array([oracle.mass_recall(sg_h[g], small_h[g]) for g in range(8)])
     assert np.abs(rec - want).max() <= RECALL_TOL
     assert (rec >= (256 - W) / (L - W)).all()
+
+
+def test_probe_read_runs(ctx):
+    print("case: read probe", flush=True)
+    buf = torch.zeros(3 << 16, dtype=torch.uint8, device="cuda")   # three 64 KiB tiles
+    ctx.fkv_probe_read(buf, False)
+    ctx.fkv_probe_read(buf, True)
+    torch.cuda.synchronize()
+    assert int(buf.sum()) == 0 and ctx.fkv_query_error() == 0
+    with pytest.raises(fk.FkvError):
+        ctx.fkv_probe_read(buf[:1000])
