@@ -57,7 +57,8 @@ def run_chain(args):
     ctx = fk.Context(max_total_tokens=L, max_seqs=1, device=0)
     layers = []
     for layer in range(n_layers):
-        Lc = L if layer <= tsp_layer else k_tsp
+        Lc, keep, kv_budget = fk.fkv_plan_layer(layer, n_layers, tsp_layer, L, 0.2, budget / L)
+        assert (keep in (0, k_tsp)) and kv_budget == min(budget, Lc)
         h = wl.make_sequence(args.seed, Lc, layer=layer, with_x=(layer == tsp_layer))
         d = {n: dev_bf16(h[n]) for n in ("q_win", "k", "v")}
         d["x"] = dev_bf16(h["x"]) if layer == tsp_layer else None

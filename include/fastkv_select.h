@@ -147,6 +147,21 @@ int fkv_gather_kv_per_head(fkv_ctx *ctx, const fkv_shape *shape, const void *k, 
  * who read the paper's merge as "top-k plus the window" pass count + W to the calls above. */
 int32_t fkv_count_from_rate(int32_t n_tokens, double rate);
 
+/* The schedule of Algorithm 1 for one layer of an n_layers-deep prefill over n_tokens context
+ * tokens: layers 0..tsp_layer see the whole context, later layers the k = round-half-up(tsp_rate *
+ * n_tokens) tokens that the TSP layer propagates (Sec. 4.2); every layer keeps a KV budget of
+ * round-half-up(kv_rate * n_tokens) tokens per KV head, counted on the original context length and
+ * capped by the tokens the layer sees (Sec. 4.4, App. B.1); both counts include the window and are
+ * never below it.  k_tsp is k at the TSP layer (run HiddenCompress there) and 0 elsewhere.
+ * Rates in (0, 1].  Host only. */
+typedef struct {
+  int32_t tokens_in;  /* tokens this layer's attention and KVCompress run over */
+  int32_t k_tsp;      /* rows HiddenCompress keeps after this layer, 0: none */
+  int32_t kv_budget;  /* tokens KVCompress keeps per KV head */
+} fkv_layer_plan;
+int fkv_plan_layer(int32_t layer, int32_t n_layers, int32_t tsp_layer, int32_t n_tokens, double tsp_rate,
+                   double kv_rate, int32_t window, fkv_layer_plan *out);
+
 /* Decode-step attention of one new query token per sequence over a KV cache, every cached token
  * visible (the consumer of the compressed cache C of Algorithm 1; Sec. 5.3 measures decoding over
  * it): out[b][h][:] = sum_t softmax_t(scale * q[b][h].k[b][h/G][t]) * v[b][h/G][t].

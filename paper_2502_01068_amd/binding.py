@@ -23,7 +23,7 @@ EXPORTS = [
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
-    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read",
+    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer",
 ]
 
 
@@ -32,6 +32,10 @@ class FkvShape(ctypes.Structure):
                 ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("window", ctypes.c_int32), ("pool_kernel", ctypes.c_int32), ("pool_mode", ctypes.c_int32),
                 ("softmax_scale", ctypes.c_float), ("causal", ctypes.c_int32)]
+
+
+class FkvLayerPlan(ctypes.Structure):
+    _fields_ = [("tokens_in", ctypes.c_int32), ("k_tsp", ctypes.c_int32), ("kv_budget", ctypes.c_int32)]
 
 
 class FkvError(RuntimeError):
@@ -77,6 +81,7 @@ def load():
     lib.fkv_decode_attention.argtypes = [vp, shp, vp, vp, vp, i32, pi32, vp, vp]
     lib.fkv_gather_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp]
     lib.fkv_decode_attention_paged.argtypes = [vp, shp, vp, vp, vp, vp, i32, i32, i64, pi32, vp, vp]
+    lib.fkv_plan_layer.argtypes = [i32, i32, i32, i32, ctypes.c_double, ctypes.c_double, i32, ctypes.POINTER(FkvLayerPlan)]
     lib.fkv_probe_read.argtypes = [vp, vp, i64, i32, vp]
     lib.fkv_index_overlap.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
     lib.fkv_mass_recall.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
@@ -125,6 +130,14 @@ def make_shape(lengths, n_q_heads=32, n_kv_heads=8, head_dim=128, window=8, pool
 def fkv_count_from_rate(n_tokens, rate):
     """Round-half-up keep count for a rate (host only)."""
     return int(load().fkv_count_from_rate(int(n_tokens), float(rate)))
+
+
+def fkv_plan_layer(layer, n_layers, tsp_layer, n_tokens, tsp_rate, kv_rate, window=8):
+    """Algorithm 1's schedule for one layer -> (tokens_in, k_tsp, kv_budget)."""
+    plan = FkvLayerPlan()
+    _check(load().fkv_plan_layer(layer, n_layers, tsp_layer, n_tokens, tsp_rate, kv_rate, window, ctypes.byref(plan)),
+           "fkv_plan_layer")
+    return plan.tokens_in, plan.k_tsp, plan.kv_budget
 
 
 def _check(status, where):

@@ -578,6 +578,22 @@ int32_t fkv_count_from_rate(int32_t n_tokens, double rate) {
   return (int32_t)x;
 }
 
+int fkv_plan_layer(int32_t layer, int32_t n_layers, int32_t tsp_layer, int32_t n_tokens, double tsp_rate,
+                   double kv_rate, int32_t window, fkv_layer_plan *out) {
+  if (!out) return FKV_ENULL;
+  if (n_layers < 1 || layer < 0 || layer >= n_layers || tsp_layer < 0 || tsp_layer >= n_layers) return FKV_EINVAL;
+  if (window < 1 || n_tokens < window) return FKV_EINVAL;
+  if (!(tsp_rate > 0.0) || !(kv_rate > 0.0) || tsp_rate > 1.0 || kv_rate > 1.0) return FKV_EINVAL;
+  int32_t k = fkv_count_from_rate(n_tokens, tsp_rate);
+  if (k < window) k = window;                       // the window is always propagated
+  int32_t budget = fkv_count_from_rate(n_tokens, kv_rate);
+  if (budget < window) budget = window;
+  out->tokens_in = layer <= tsp_layer ? n_tokens : k;
+  out->k_tsp = layer == tsp_layer ? k : 0;
+  out->kv_budget = budget < out->tokens_in ? budget : out->tokens_in;
+  return FKV_OK;
+}
+
 namespace {
 struct Paging {  // block-table addressing of a paged cache; table == nullptr: none
   const int32_t *table;

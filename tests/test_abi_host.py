@@ -159,3 +159,22 @@ def test_count_from_rate_matches_the_stated_counts(lib):
     assert lib.fkv_count_from_rate(-1, 0.2) == -1 and lib.fkv_count_from_rate(10, -0.1) == -1
     assert lib.fkv_count_from_rate(10, float("nan")) == -1
     assert lib.fkv_score_heads(None, None, None, None, None, None) == fk.FKV_ENULL
+
+
+def test_plan_layer_follows_algorithm_1(lib):
+    # the three evaluated models (Sec. 5.1, App. C.1): layers, TSP layer; TSP rate 20 % gives the
+    # stated 60 % prefill compute rate for each of them
+    for n_layers, tsp in ((32, 15), (36, 17), (40, 19)):
+        plans = [fk.fkv_plan_layer(l, n_layers, tsp, 32768, 0.2, 0.0625) for l in range(n_layers)]
+        assert [p[0] for p in plans] == [32768] * (tsp + 1) + [6554] * (n_layers - tsp - 1)
+        assert [p[1] for p in plans] == [0] * tsp + [6554] + [0] * (n_layers - tsp - 1)
+        assert all(p[2] == 2048 for p in plans)
+        assert abs(sum(p[0] for p in plans) / (n_layers * 32768) - 0.6) < 1e-4
+    assert fk.fkv_plan_layer(15, 32, 15, 131072, 0.2, 0.1) == (131072, 26214, 13107)
+    assert fk.fkv_plan_layer(20, 32, 15, 131072, 0.2, 0.5) == (26214, 0, 26214)      # budget capped by what the layer sees
+    assert fk.fkv_plan_layer(3, 4, 1, 16, 0.01, 0.01) == (8, 0, 8)                   # never below the window
+    p = fk.FkvLayerPlan()
+    assert lib.fkv_plan_layer(32, 32, 15, 100, 0.2, 0.1, 8, ctypes.byref(p)) == fk.FKV_EINVAL
+    assert lib.fkv_plan_layer(0, 32, 15, 100, 0.0, 0.1, 8, ctypes.byref(p)) == fk.FKV_EINVAL
+    assert lib.fkv_plan_layer(0, 32, 15, 4, 0.2, 0.1, 8, ctypes.byref(p)) == fk.FKV_EINVAL
+    assert lib.fkv_plan_layer(0, 32, 15, 100, 0.2, 0.1, 8, None) == fk.FKV_ENULL
