@@ -87,3 +87,39 @@ def test_out_of_pool_table_entries_write_nothing(ctx):
     want[2] = s["k"][0:16]
     want[4] = s["k"][48:64]
     np.testing.assert_array_equal(host_bits(kp), want)
+
+
+def test_paged_full_size_pipeline(ctx):
+    """Config-2 shape end to end: score, select, KVCompress into 16-token pages, decode over the
+    pages; checked against the compact path of the same call sequence and, on sampled slots,
+    against the source rows."""
+    print("case: paged pipeline L=32768 budget=2048 page=16", flush=True)
+    L, budget, ps, Hkv = 32768, 2048, 16, 8
+    s = wl.make_sequence(70, L, with_x=False)
+    shape = fk.make_shape(L, pool_mode="avg")
+    q, k, v = dev_bf16(s["q_win"]), dev_bf16(s["k"]), dev_bf16(s["v"])
+    sg, _ = ctx.fkv_score_window(shape, q, k, want_tsp=False)
+    idx = ctx.fkv_select_topk(shape, sg, budget)
+    n_pages = budget // ps + 37
+    rng = np.random.default_rng(70)
+    table = rng.permutation(n_pages)[: budget // ps].astype(np.int32)[None, :]
+    kp = torch.zeros((n_pages, ps, Hkv, 128), dtype=torch.bfloat16, device="cuda")
+    vp = torch.zeros_like(kp)
+    ctx.fkv_gather_kv_paged(shape, k, v, idx, budget, torch.from_numpy(table).cuda(), kp, vp)
+    kc, vc = ctx.fkv_gather_kv(shape, k, v, idx, budget)
+    # logical view of the pages == compact cache, bit for bit
+    order = torch.from_numpy(table[0]).long().cuda()
+    view_k = kp[order].reshape(budget, Hkv, 128).permute(1, 0, 2)
+    view_v = vp[order].reshape(budget, Hkv, 128).permute(1, 0, 2)
+    assert torch.equal(view_k.view(torch.int16), kc.view(torch.int16))
+    assert torch.equal(view_v.view(torch.int16), vc.view(torch.int16))
+    # sampled slots against the source rows through the oracle's addressing
+    idx_h, kp_h = idx.cpu().numpy(), host_bits(kp)
+    for g, t in [(0, 0), (3, 17), (7, 2047), (5, 1024), (2, 999)]:
+        np.testing.assert_array_equal(kp_h[table[0, t // ps], t % ps, g], s["k"][idx_h[g, t], g])
+    untouched = np.setdiff1d(np.arange(n_pages), table[0])
+    assert not kp_h[untouched].any()
+    qd = dev_bf16(wl.normal_bf16(71, 0, "q_win", (1, 32, 128)))
+    a = ctx.fkv_decode_attention_paged(shape, qd, kp, vp, torch.from_numpy(table).cuda(), budget)
+    b = ctx.fkv_decode_attention(shape, qd, kc, vc, budget, "compact")
+    assert torch.equal(a, b)

@@ -302,6 +302,25 @@ def test_compress_kv_ragged_batch(ctx):
                  [wl.round_half_up(0.2 * L) for L in lengths], "max", "ragged")
 
 
+@pytest.mark.parametrize("score_path", [0, 1])
+def test_compress_kv_largest_batch(score_path):
+    """FKV_MAX_SEQS sequences in one call, lengths from the window alone up to a few tiles."""
+    rng = np.random.default_rng(5)
+    lengths = [8, 9, 40, 41] + [int(x) for x in rng.integers(8, 400, size=60)]
+    assert len(lengths) == 64
+    print("case: compress_kv 64 sequences, score path %d" % score_path, flush=True)
+    batch = wl.make_batch(9, lengths, n_heavy=2)
+    budgets = [max(8, L // 3) for L in lengths]
+    ktsps = [max(8, wl.round_half_up(0.2 * L)) for L in lengths]
+    c = fk.Context(max_total_tokens=sum(lengths), max_seqs=64)
+    try:
+        c.fkv_set_score_path(score_path)
+        _check_layer(c, batch["seqs"], lengths, budgets, ktsps, "max", "64 sequences")
+        assert c.fkv_query_error() == 0
+    finally:
+        c.close()
+
+
 @pytest.mark.parametrize("pool_mode", ["max", "avg"])
 def test_per_head_retention(ctx, pool_mode):
     # head-wise variant: pooled per-head scores (Eq. 1), one index set per query head, per-head K/V copies
