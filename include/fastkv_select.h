@@ -24,6 +24,8 @@
  *     context's workspace).  Calls on different contexts may run concurrently on different
  *     streams; while several contexts exist on a device, their single-pass score launches are
  *     chained on the GPU through an event (that event wait cannot be captured into a graph).
+ *   - The calling thread's current HIP device must be the context's device and `stream` must
+ *     belong to it; the library does not switch devices.
  *   - bf16 tensors are raw 16-bit patterns.  Scores are fp32, indices int32.
  *
  * Tensor layouts (B = n_seq sequences packed along tokens, T_b = cu_seqlens[b], sum L = T_B)
