@@ -243,6 +243,13 @@ int fkv_set_score_path(fkv_ctx *ctx, int mode);
  * competing for the device's compute units for that long. */
 int fkv_query_error(fkv_ctx *ctx, int32_t *flag_out);
 
+/* fkv_set_wait_limit: bound of that wait in microseconds (0 restores the 2 s default, at most 60 s).
+ * A block that gives up still leaves the kernel normally and the grid's counters re-arm themselves,
+ * so the next call works; a tiny limit is how the failure path is exercised.  fkv_clear_error
+ * synchronises the device and resets the flag. */
+int fkv_set_wait_limit(fkv_ctx *ctx, int64_t microseconds);
+int fkv_clear_error(fkv_ctx *ctx);
+
 /* Per-kernel device timing for benchmarks.  While enabled, every launch is bracketed by
  * HIP events on the caller's stream (within one call the end event of a launch starts the next
  * launch's interval, so each figure includes the event record that precedes the launch: about

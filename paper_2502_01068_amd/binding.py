@@ -23,7 +23,7 @@ EXPORTS = [
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
-    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer",
+    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error",
 ]
 
 
@@ -89,6 +89,8 @@ def load():
     lib.fkv_count_from_rate.argtypes = [i32, ctypes.c_double]
     lib.fkv_set_score_path.argtypes = [vp, ctypes.c_int]
     lib.fkv_query_error.argtypes = [vp, pi32]
+    lib.fkv_set_wait_limit.argtypes = [vp, i64]
+    lib.fkv_clear_error.argtypes = [vp]
     lib.fkv_profile_kernels.restype = ctypes.c_int
     lib.fkv_profile_kernel_name.restype = ctypes.c_char_p
     lib.fkv_profile_kernel_name.argtypes = [ctypes.c_int]
@@ -378,6 +380,12 @@ class Context:
     def fkv_set_score_path(self, mode):
         """0 auto, 1 two-pass kernels, 2 single-pass resident-grid kernel."""
         _check(load().fkv_set_score_path(self.handle, int(mode)), "fkv_set_score_path")
+
+    def fkv_set_wait_limit(self, microseconds):
+        _check(load().fkv_set_wait_limit(self.handle, int(microseconds)), "fkv_set_wait_limit")
+
+    def fkv_clear_error(self):
+        _check(load().fkv_clear_error(self.handle), "fkv_clear_error")
 
     def fkv_query_error(self):
         flag = ctypes.c_int32(0)

@@ -65,6 +65,7 @@ struct fkv_ctx {
   uint8_t *ws;
   int n_cu;            // compute units x resident blocks per CU of the single-pass score kernel
   int score_path;      // 0 auto, 1 two-pass kernels, 2 single-pass resident grid
+  unsigned long long wait_ticks;  // bound of the single-pass kernel's grid wait, 100 MHz ticks
   bool prof_on;
   std::vector<EventPair> ev_pool;
   size_t ev_used;
@@ -234,7 +235,7 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
       f.cpartial_stride = kMaxClusters;
       f.n_wg = total;
       f.n_clusters = clusters;
-      f.timeout_ticks = 200000000ull;  // 2 s
+      f.timeout_ticks = ctx->wait_ticks;
       FusedGate &gate = g_gate[ctx->device & 15];
       std::lock_guard<std::mutex> lock(gate.mu);
       const bool chained = gate.n_ctx > 1 && gate.last != nullptr;
@@ -409,6 +410,7 @@ int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_
   c->lay = ws_layout(max_total_tokens, max_seqs);
   c->ws = nullptr;
   c->score_path = 0;
+  c->wait_ticks = 200000000ull;  // 2 s
   {
     hipDeviceProp_t prop;
     e = hipGetDeviceProperties(&prop, device);
@@ -829,6 +831,19 @@ int fkv_query_error(fkv_ctx *ctx, int32_t *flag_out) {
   if (e != hipSuccess) return hip_fail(e);
   *flag_out = (int32_t)v;
   return FKV_OK;
+}
+
+int fkv_set_wait_limit(fkv_ctx *ctx, int64_t microseconds) {
+  if (!ctx) return FKV_ENULL;
+  if (microseconds < 0 || microseconds > 60000000) return FKV_EINVAL;
+  ctx->wait_ticks = microseconds == 0 ? 200000000ull : (unsigned long long)microseconds * 100ull;
+  return FKV_OK;
+}
+
+int fkv_clear_error(fkv_ctx *ctx) {
+  if (!ctx) return FKV_ENULL;
+  const hipError_t e = hipMemset(ctx->ws + ctx->lay.counters + kCtrError * sizeof(unsigned), 0, sizeof(unsigned));
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 
 int fkv_profile_kernels(void) { return KID_COUNT; }

@@ -384,6 +384,36 @@ def test_single_pass_path_is_taken_and_rejects_oversize(ctx):
     c2.close()
 
 
+def test_grid_wait_gives_up_cleanly_and_recovers():
+    """Failure path of the single-pass kernel, forced from the host with a wait limit of 10 ns: blocks
+    that have to wait give up, raise the sticky flag and leave the kernel normally; with the limit
+    restored the very next call is correct again."""
+    print("case: single-pass grid wait limit", flush=True)
+    L = 8192
+    s = wl.make_sequence(21, L, with_x=False)
+    c = fk.Context(max_total_tokens=L, max_seqs=1)
+    try:
+        shape = fk.make_shape(L, pool_mode="max")
+        q, k = dev_bf16(s["q_win"]), dev_bf16(s["k"])
+        c.fkv_set_score_path(1)
+        want_g, want_t = (t.clone() for t in c.fkv_score_window(shape, q, k))
+        c.fkv_set_score_path(2)
+        assert c.fkv_query_error() == 0
+        c.fkv_set_wait_limit(1)   # 1 us: far below the exchange's round trips
+        for _ in range(3):
+            c.fkv_score_window(shape, q, k)
+        assert c.fkv_query_error() == 1     # also proves the launches drained: the query synchronises
+        c.fkv_clear_error()
+        c.fkv_set_wait_limit(0)
+        for _ in range(2):
+            got_g, got_t = c.fkv_score_window(shape, q, k)
+            assert_scores_close(got_g.cpu().numpy(), want_g.cpu().numpy(), "scores_group after recovery")
+            assert_scores_close(got_t.cpu().numpy(), want_t.cpu().numpy(), "scores_tsp after recovery")
+        assert c.fkv_query_error() == 0
+    finally:
+        c.close()
+
+
 def test_chain_small(ctx):
     # Algorithm 1 at reduced size: 6 layers, TSP layer 2; layers after it run on the kept tokens.
     print("case: chain small", flush=True)
