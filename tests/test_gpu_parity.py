@@ -414,6 +414,41 @@ def test_grid_wait_gives_up_cleanly_and_recovers():
         c.close()
 
 
+def test_two_contexts_on_two_streams():
+    """Two calls in flight: two contexts, two streams, single-pass score launches chained on the GPU.
+    Every interleaved call must reproduce the result of the same call run alone, bit for bit."""
+    print("case: two contexts on two streams", flush=True)
+    L, budget, k_tsp = 12000, 512, 2400
+    seqs = [wl.make_sequence(31 + i, L) for i in range(2)]
+    ctxs = [fk.Context(max_total_tokens=L, max_seqs=1) for _ in range(2)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    try:
+        shape = fk.make_shape(L, pool_mode="avg")
+        dev = [{n: dev_bf16(s[n]) for n in ("q_win", "k", "v", "x")} for s in seqs]
+        alone = []
+        for c, d in zip(ctxs, dev):
+            out = c.fkv_compress_kv(shape, d["q_win"], d["k"], d["v"], budget, x=d["x"], k_tsp_per_seq=k_tsp)
+            alone.append({n: t.clone() for n, t in out.items()})
+        torch.cuda.synchronize()
+        outs = [None, None]
+        for st in streams:
+            st.wait_stream(torch.cuda.current_stream())
+        for it in range(6):
+            for i in (0, 1):
+                with torch.cuda.stream(streams[i]):
+                    outs[i] = ctxs[i].fkv_compress_kv(shape, dev[i]["q_win"], dev[i]["k"], dev[i]["v"], budget,
+                                                      x=dev[i]["x"], k_tsp_per_seq=k_tsp, out=outs[i])
+        torch.cuda.synchronize()
+        for i in (0, 1):
+            for n, t in alone[i].items():
+                a, b = (u.view(torch.int16) if u.dtype == torch.bfloat16 else u for u in (t, outs[i][n]))
+                assert torch.equal(a, b), (i, n)
+            assert ctxs[i].fkv_query_error() == 0
+    finally:
+        for c in ctxs:
+            c.close()
+
+
 def test_chain_small(ctx):
     # Algorithm 1 at reduced size: 6 layers, TSP layer 2; layers after it run on the kept tokens.
     print("case: chain small", flush=True)
