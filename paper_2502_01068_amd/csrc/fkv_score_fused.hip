@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   const int o0 = local * f.own[b], o1 = min(P, o0 + f.own[b]);  // owned prefix tokens
   const bool last = local == n_ranges - 1;                      // also owns the window columns
   const int c0 = o0 - r;                                        // first computed token (may be < 0)
-  const int c1 = last ? Lb : o1 + r;
+  const int c1 = last ? max(Lb, o1 + r) : o1 + r;               // the pooling halo may reach past the window (r > W)
   const int n_sub = (c1 - c0 + kSub - 1) / kSub;                // <= kFusedSub (host guarantees)
   uint8_t *stage = lds_all + wave * kStageBytes;
   const int g = wave;

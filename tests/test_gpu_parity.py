@@ -60,6 +60,8 @@ def test_scores_config1(ctx, pool_mode):
     (300, 3, 3, 1, 1, True, 0.0),       # W=1, kernel 1: plain softmax row
     (500, 12, 4, 7, 9, True, 0.05),     # odd W, G=3, custom scale
     (513, 16, 8, 8, 31, True, 0.0),     # widest supported pooling kernel
+    (1267, 3, 3, 4, 27, True, 0.0),     # pooling radius beyond the window: the halo of the last tokens runs past L
+    (200, 4, 4, 1, 31, True, 0.0),      # ... with a one-token window
 ])
 @pytest.mark.parametrize("pool_mode", ["max", "avg"])
 def test_scores_shapes(ctx, L, Hq, Hkv, W, pk, causal, scale, pool_mode):
@@ -447,6 +449,52 @@ def test_two_contexts_on_two_streams():
     finally:
         for c in ctxs:
             c.close()
+
+
+@pytest.mark.parametrize("case", range(64))
+def test_random_valid_shapes(ctx, case):
+    """Seeded random draws over everything the boundary accepts: head counts, window, pooling kernel and
+    mode, mask, scale, ragged batches, keep counts; score -> select -> K/V gather against the oracle."""
+    rng = np.random.default_rng(1000 + case)
+    Hkv, G, W = int(rng.integers(1, 9)), int(rng.integers(1, 5)), int(rng.integers(1, 9))
+    Hq = Hkv * G
+    pk = int(rng.integers(0, 16)) * 2 + 1
+    causal, pool_mode = bool(rng.integers(0, 2)), ("max", "avg")[int(rng.integers(0, 2))]
+    scale = float(rng.choice([0.0, 0.03, 0.1]))   # larger scales push the planted-key rows' other scores below fp32's normal range
+    B = int(rng.integers(1, 6))
+    lengths = [int(rng.integers(W, 1500)) for _ in range(B)]
+    if case % 5 == 0:
+        lengths[0] = W                      # a sequence that is only its window
+    ks = [int(rng.integers(W, L + 1)) for L in lengths]
+    print("case %d: Hq=%d Hkv=%d W=%d pk=%d %s causal=%s scale=%g lengths=%s ks=%s" % (
+        case, Hq, Hkv, W, pk, pool_mode, causal, scale, lengths, ks), flush=True)
+    seqs = [wl.make_sequence(2000 + case, L, window=W, n_q_heads=Hq, n_kv_heads=Hkv, n_heavy=min(4, L - W),
+                             seq=b, with_x=False) for b, L in enumerate(lengths)]
+    shape = fk.make_shape(lengths if B > 1 else lengths[0], n_q_heads=Hq, n_kv_heads=Hkv, window=W,
+                          pool_kernel=pk, pool_mode=pool_mode, causal=causal, softmax_scale=scale)
+    q = dev_bf16(np.stack([s_["q_win"] for s_ in seqs]))
+    k = dev_bf16(np.concatenate([s_["k"] for s_ in seqs]))
+    v = dev_bf16(np.concatenate([s_["v"] for s_ in seqs]))
+    sg, st = ctx.fkv_score_window(shape, q, k)
+    idx = ctx.fkv_select_topk(shape, sg, ks)
+    ko, vo = ctx.fkv_gather_kv(shape, k, v, idx, ks)
+    sg_h, st_h, idx_h, ko_h, vo_h = sg.cpu().numpy(), st.cpu().numpy(), idx.cpu().numpy(), host_bits(ko), host_bits(vo)
+    col = o = 0
+    for b, (s_, L) in enumerate(zip(seqs, lengths)):
+        P = L - W
+        ref = oracle.score_window(s_["q_win"], s_["k"], pk, pool_mode, scale=(scale or None), causal=causal,
+                                  precision="f64")
+        assert_scores_close(sg_h[:, col:col + P], ref["scores_group"], "scores_group seq %d" % b)
+        assert_scores_close(st_h[col:col + P], ref["scores_tsp"], "scores_tsp seq %d" % b)
+        for g in range(Hkv):
+            mine = idx_h[g, o:o + ks[b]]
+            np.testing.assert_array_equal(mine, oracle.select_topk(sg_h[g, col:col + P], W, ks[b]))
+            assert_index_set(mine, oracle.select_topk(ref["scores_group"][g].astype(np.float32), W, ks[b]),
+                             ref["scores_group"][g], W, "seq %d g %d" % (b, g))
+            np.testing.assert_array_equal(ko_h[g, o:o + ks[b]], s_["k"][mine, g])
+            np.testing.assert_array_equal(vo_h[g, o:o + ks[b]], s_["v"][mine, g])
+        col += P
+        o += ks[b]
 
 
 def test_chain_small(ctx):
