@@ -151,3 +151,29 @@ def test_random_decode(ctx, case):
         err = np.abs(out_tm[b] - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
         assert err.max() <= 1e-3, (b, err.max())
         off += n
+
+
+@pytest.mark.parametrize("case", range(10))
+def test_random_medium_batches_scores(ctx, case):
+    """Ragged batches of a few thousand to tens of thousands of tokens: many blocks and clusters per
+    sequence on the single-pass path (totals under its limit) and the two-pass path (totals above)."""
+    from parity import assert_scores_close
+    rng = np.random.default_rng(7000 + case)
+    B = int(rng.integers(1, 8))
+    budget = 36000 if case % 2 == 0 else 90000
+    cuts = np.sort(rng.integers(0, budget, size=B - 1)) if B > 1 else np.array([], np.int64)
+    lengths = [max(8, int(x)) for x in np.diff(np.concatenate([[0], cuts, [budget]]))]
+    pool_mode = ("avg", "max")[case % 2]
+    pk = int(rng.choice([1, 7, 7, 15]))
+    print("case %d: lengths=%s pool=%s %d" % (case, lengths, pool_mode, pk), flush=True)
+    batch = wl.make_batch(7000 + case, lengths, with_v=False, with_x=False)
+    shape = fk.make_shape(lengths if B > 1 else lengths[0], pool_mode=pool_mode, pool_kernel=pk)
+    sg, st = ctx.fkv_score_window(shape, dev_bf16(batch["q_win"]), dev_bf16(batch["k"]))
+    sg, st = sg.cpu().numpy(), st.cpu().numpy()
+    col = 0
+    for b, s_ in enumerate(batch["seqs"]):
+        P = lengths[b] - 8
+        ref = oracle.score_window(s_["q_win"], s_["k"], pk, pool_mode, precision="f32")
+        assert_scores_close(sg[:, col:col + P], ref["scores_group"], "scores_group seq %d" % b)
+        assert_scores_close(st[col:col + P], ref["scores_tsp"], "scores_tsp seq %d" % b)
+        col += P
