@@ -120,7 +120,8 @@ int fkv_select_topk(fkv_ctx *ctx, const fkv_shape *shape, const float *scores, i
 
 /* gather_rows(X, idx): out[o_b + t][:] = x[T_b + idx[o_b + t]][:] for t < k_b, where
  * o_b = sum_{b'<b} k_b' (HiddenCompress, App. B.1).  Rows are copied bit for bit.
- * Indices must lie in [0, L_b); they are not checked on the device. */
+ * Indices must lie in [0, L_b); the kernels clamp an index outside that range into it (a wrong
+ * row is copied, nothing is read out of bounds).  The same holds for every gather below. */
 int fkv_gather_rows(fkv_ctx *ctx, const fkv_shape *shape, const void *x, size_t row_bytes,
                     const int32_t *idx, const int32_t *k_per_seq, void *out, void *stream);
 

@@ -53,7 +53,9 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(GatherArgs a) {
       else { t = c / cpr; col = c - t * cpr; }
       int b = 0;
       while (b + 1 < a.n_seq && (int)t >= job.cnt_off[b + 1]) ++b;
-      const size_t tok = (size_t)a.cu[b] + (size_t)idx[t];
+      // an index outside its sequence is clamped into it: a wrong row, never an out-of-bounds read
+      const int local = min(max(idx[t], 0), a.cu[b + 1] - a.cu[b] - 1);
+      const size_t tok = (size_t)a.cu[b] + (size_t)local;
 #if FKV_GATHER_NT
       val[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src_h + tok * job.src_row_stride) + col);
 #else
@@ -93,7 +95,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather_paged(PagedGatherArgs
       while (b + 1 < a.n_seq && (int)t >= a.cnt_off[b + 1]) ++b;
       const uint32_t tl = t - a.cnt_off[b];
       const int page = a.block_table[(size_t)b * a.max_pages + (tl >> a.page_shift)];
-      const size_t tok = (size_t)a.cu[b] + (size_t)a.idx[(size_t)g * a.total_rows + t];
+      const int local = min(max(a.idx[(size_t)g * a.total_rows + t], 0), a.cu[b + 1] - a.cu[b] - 1);
+      const size_t tok = (size_t)a.cu[b] + (size_t)local;
       val[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (tok * a.Hkv + g) * (kHeadDim * 2)) + col);
       if (page >= 0 && page < a.n_pages) {
         const size_t slot = ((size_t)page << a.page_shift) + (tl & ((1u << a.page_shift) - 1u));

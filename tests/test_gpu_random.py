@@ -177,3 +177,13 @@ def test_random_medium_batches_scores(ctx, case):
         assert_scores_close(sg[:, col:col + P], ref["scores_group"], "scores_group seq %d" % b)
         assert_scores_close(st[col:col + P], ref["scores_tsp"], "scores_tsp seq %d" % b)
         col += P
+
+
+def test_gather_clamps_indices_outside_the_sequence(ctx):
+    print("case: gather with out-of-range indices", flush=True)
+    lengths, ks = [100, 60], [8, 8]
+    x = np.arange(160 * 8, dtype=np.uint16).reshape(160, 8)
+    idx = np.array([0, 5, 99, 100, 2 ** 30, -1, -2 ** 31, 50, 0, 59, 60, 61, 10 ** 9, -5, 1, 2], np.int32)
+    out = host_bits(ctx.fkv_gather_rows(fk.make_shape(lengths), dev_bf16(x), torch.from_numpy(idx).cuda(), ks))
+    want = np.concatenate([x[np.clip(idx[:8], 0, 99)], x[100 + np.clip(idx[8:], 0, 59)]])
+    np.testing.assert_array_equal(out, want)
