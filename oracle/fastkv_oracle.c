@@ -27,6 +27,14 @@
  *    (the avg divisor is always the kernel size);
  *  - head g*G .. g*G+G-1 share KV head g;
  *  - |kept| = k counts the W window tokens; ties go to the lower index.
+ *
+ * Pins: every function here is checked in tests/test_oracle_pins.py against something other
+ * than itself (textbook softmax and library pooling / sort / index ops, closed forms for
+ * equal keys, the causal corner by hand, exhaustive subset enumeration for the top-k).
+ * Parity unpinned by the paper itself: it prints no value or worked example for the
+ * selection, so the readings above about the pooling type and boundary, mean rather than
+ * sum over heads, k counting the window and KVCompress keeping the window rest on the
+ * text alone.
  */
 #include <math.h>
 #include <stdint.h>
