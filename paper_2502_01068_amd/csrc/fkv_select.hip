@@ -84,8 +84,8 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
     for (int ch = 0; ch < n_chunks; ++ch) {
       if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
 #pragma unroll
-      for (int e = 0; e < kKpt; ++e)  // branch-free: empty slots (key 0) count into the spare bin
-        atomicAdd(&hist[key[e] ? (key[e] - lo) >> shift : (uint32_t)kBins], 1u);
+      for (int e = 0; e < kKpt; ++e)  // branch-free: empty slots (key 0) count into a spare word per lane
+        atomicAdd(&hist[key[e] ? (key[e] - lo) >> shift : (uint32_t)kBins + (lane & 31)], 1u);
     }
     __syncthreads();
     FKV_TICK(8);
@@ -161,7 +161,8 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
-  __shared__ uint32_t hist[kBins + 1];  // + spare bin for empty key slots
+  __shared__ uint32_t hist[kBins + 32];  // + spare words for empty key slots (never read; one per bank, so a
+                                         // short row's many empty slots do not pile onto one address)
   __shared__ __attribute__((aligned(16))) uint32_t scan_tbl[kSelWaves * 64 * kMaxKpt];  // 128 KiB: scan tables / output staging
   __shared__ uint32_t wsum[2 * kSelWaves];
   __shared__ uint32_t bcast[8 + 64];  // broadcast slots, then one sink word per lane
