@@ -177,6 +177,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="config2_L32768", choices=sorted(WORKLOADS) + ["config5_chain", "decode"])
     ap.add_argument("--pool", default="avg", choices=["avg", "max"])
+    ap.add_argument("--pool-kernel", type=int, default=7, help="odd pooling kernel size (the paper uses 7)")
     ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated over the steps")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -205,7 +206,7 @@ def main():
     W = 8
     torch.cuda.set_device(0)
     ctx = fk.Context(max_total_tokens=L, max_seqs=1, device=0)
-    shape = fk.make_shape(L, pool_mode=args.pool)
+    shape = fk.make_shape(L, pool_mode=args.pool, pool_kernel=args.pool_kernel)
 
     t_gen = time.time()
     host0 = wl.make_sequence(args.seed, L)
@@ -349,9 +350,9 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16 inputs, fp32 accumulate and scores, int32 indices",
         "data": "synthetic (seeded N(0,1) bf16 + 1% planted heavy keys)",
-        "config": {"workload": "%s: 1 layer, batch 1, L=%d, 32 q / 8 kv heads, d=128, hidden 4096, W=8, pool %s 7, "
-                               "k_tsp=%d, kv budget=%d, %d rotating input sets" % (args.workload, L, args.pool, k_tsp,
-                                                                                  budget, len(sets))},
+        "config": {"workload": "%s: 1 layer, batch 1, L=%d, 32 q / 8 kv heads, d=128, hidden 4096, W=8, pool %s %d, "
+                               "k_tsp=%d, kv budget=%d, %d rotating input sets" % (args.workload, L, args.pool,
+                                                                                  args.pool_kernel, k_tsp, budget, len(sets))},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": dom_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_us": per_kernel_us[dominant]},
@@ -376,7 +377,7 @@ def main():
         o = outs[0]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        ref = oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, 7, args.pool, x=host0["x"],
+        ref = oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, args.pool_kernel, args.pool, x=host0["x"],
                                  k_tsp=k_tsp)
         t_oracle = time.perf_counter() - t0
         if not args.no_cpu_baseline:
@@ -385,7 +386,7 @@ def main():
             reps = max(1, min(20, int(1.5 / max(t_oracle, 1e-3))))
             t0 = time.perf_counter()
             for _ in range(reps):
-                oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, 7, args.pool, x=host0["x"], k_tsp=k_tsp)
+                oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, args.pool_kernel, args.pool, x=host0["x"], k_tsp=k_tsp)
             t_mean = (time.perf_counter() - t0) / reps
             result["cpu_baseline"] = {"value": L / t_mean, "unit": "tokens/s", "cores": oracle.max_threads(),
                                       "kind": "oracle",
