@@ -105,3 +105,56 @@ def test_config4_ragged(budget):
         print("  seq %d ok" % b, flush=True)
     print("  tolerance-band flips %d" % flips, flush=True)
     ctx.close()
+
+
+def test_config2_repeatability_under_load():
+    """The single-pass kernel's grid exchange and the select's tie handling must not depend on
+    timing: 1500 back-to-back calls over 3 rotating input sets, two contexts alternating on two
+    streams for the second half, every output compared with the first call's on the device."""
+    print("case: repeatability L=32768, 1500 calls", flush=True)
+    L, k_tsp, budget = 32768, 6554, 2048
+    shape = fk.make_shape(L, pool_mode="max")
+    gen = torch.Generator(device="cuda")
+    sets = []
+    for i in range(3):
+        gen.manual_seed(100 + i)
+        sets.append(dict(q=torch.randn((8, 32, 128), device="cuda", generator=gen).bfloat16(),
+                         k=torch.randn((L, 8, 128), device="cuda", generator=gen).bfloat16(),
+                         v=torch.randn((L, 8, 128), device="cuda", generator=gen).bfloat16(),
+                         x=torch.randn((L, 4096), device="cuda", generator=gen).bfloat16()))
+    ctxs = [fk.Context(max_total_tokens=L, max_seqs=1) for _ in range(2)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    try:
+        def call(c, s, out=None):
+            return c.fkv_compress_kv(shape, s["q"], s["k"], s["v"], budget, x=s["x"], k_tsp_per_seq=k_tsp, out=out)
+        first = [{n: t.clone() for n, t in call(ctxs[0], s).items()} for s in sets]
+        bad = torch.zeros((), dtype=torch.int64, device="cuda")
+        outs = [None, None]
+
+        def check(o, ref):
+            nonlocal bad
+            bad += (o["idx_kv"] != ref["idx_kv"]).sum() + (o["idx_tsp"] != ref["idx_tsp"]).sum()
+            bad += (o["x_out"].view(torch.int16) != ref["x_out"].view(torch.int16)).sum()
+
+        for it in range(750):
+            outs[0] = call(ctxs[0], sets[it % 3], outs[0])
+            check(outs[0], first[it % 3])
+        torch.cuda.synchronize()
+        assert int(bad) == 0
+        print("  one stream: ok", flush=True)
+        bads = [torch.zeros((), dtype=torch.int64, device="cuda") for _ in range(2)]
+        for st in streams:
+            st.wait_stream(torch.cuda.current_stream())
+        for it in range(375):
+            for i in (0, 1):
+                with torch.cuda.stream(streams[i]):
+                    j = (it + i) % 3
+                    outs[i] = call(ctxs[i], sets[j], outs[i])
+                    bads[i] += (outs[i]["idx_kv"] != first[j]["idx_kv"]).sum() + (outs[i]["idx_tsp"] != first[j]["idx_tsp"]).sum()
+        torch.cuda.synchronize()
+        assert int(bads[0]) == 0 and int(bads[1]) == 0
+        for c in ctxs:
+            assert c.fkv_query_error() == 0
+    finally:
+        for c in ctxs:
+            c.close()
