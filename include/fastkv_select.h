@@ -39,9 +39,10 @@
  *   k_out, v_out [Hkv][sum budget][d] bf16
  *   x_out        [sum k][row_bytes]
  *
- * Supported shapes: head_dim = 128; 1 <= W <= 8; Hq = G*Hkv with 1 <= G <= 4;
+ * Supported shapes: head_dim = 128; 1 <= W <= 8; Hq = G*Hkv with 1 <= G <= 8;
  * 1 <= Hkv <= 8; odd pool_kernel <= 31; B <= FKV_MAX_SEQS.  Anything else returns
- * FKV_EUNSUPPORTED.
+ * FKV_EUNSUPPORTED.  (Groups of more than 4 query heads take two passes of the matrix tile
+ * per KV head; with more than 8 such half-groups the two-pass score kernels are used.)
  */
 #ifndef FASTKV_SELECT_H
 #define FASTKV_SELECT_H

@@ -28,15 +28,15 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
   const int chunk = stats_chunk_tokens();
   w.max_stat_blocks = (int)((max_tokens + chunk - 1) / chunk) + max_seqs;
   size_t off = 0;
-  w.partial = off;      off += align_up((size_t)w.max_stat_blocks * kMaxKvHeads * kRowsPerGroup * sizeof(float2));
-  w.rowstat = off;      off += align_up((size_t)max_seqs * kMaxKvHeads * kRowsPerGroup * sizeof(float));
+  w.partial = off;      off += align_up((size_t)w.max_stat_blocks * kMaxVGroups * kRowsPerGroup * sizeof(float2));
+  w.rowstat = off;      off += align_up((size_t)max_seqs * kMaxVGroups * kRowsPerGroup * sizeof(float));
   w.scores_group = off; off += align_up((size_t)max_tokens * kMaxKvHeads * sizeof(float));
   w.scores_tsp = off;   off += align_up((size_t)max_tokens * sizeof(float));
   w.counters = off;     off += align_up((size_t)kNumCounters * sizeof(unsigned));
   w.bpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxFusedBlocks * sizeof(float2));
   w.cpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxClusters * sizeof(float2));
   w.sel_long = off;     off += align_up((size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
-  w.dec_part = off;     off += align_up((size_t)max_seqs * kMaxKvHeads * kMaxGroup * kDecodeMaxSplits * (kHeadDim + 2) * sizeof(float));
+  w.dec_part = off;     off += align_up((size_t)max_seqs * kMaxKvHeads * kMaxReal * kDecodeMaxSplits * (kHeadDim + 2) * sizeof(float));
   w.total = off;
   return w;
 }
@@ -88,6 +88,7 @@ struct Resolved {
   int n_seq;
   int cu[FKV_MAX_SEQS + 1];
   int W, Hq, Hkv, G;
+  int V, vsh;  // virtual groups of at most 4 query heads (two per KV head when G > 4)
   int64_t total, sum_p;
 };
 
@@ -104,7 +105,7 @@ int resolve(const fkv_shape *s, Resolved *r) {
   if (s->n_seq > FKV_MAX_SEQS) return FKV_EUNSUPPORTED;
   if (s->head_dim != kHeadDim) return FKV_EUNSUPPORTED;
   if (s->window > kMaxWindow) return FKV_EUNSUPPORTED;
-  if (s->n_kv_heads > kMaxKvHeads || s->n_q_heads / s->n_kv_heads > kMaxGroup) return FKV_EUNSUPPORTED;
+  if (s->n_kv_heads > kMaxKvHeads || s->n_q_heads / s->n_kv_heads > kMaxReal) return FKV_EUNSUPPORTED;
   if (s->pool_kernel > kMaxPoolKernel) return FKV_EUNSUPPORTED;
   r->n_seq = s->n_seq;
   if (s->cu_seqlens) {
@@ -120,6 +121,8 @@ int resolve(const fkv_shape *s, Resolved *r) {
   r->Hq = s->n_q_heads;
   r->Hkv = s->n_kv_heads;
   r->G = r->Hq / r->Hkv;
+  r->vsh = r->G > kMaxGroup ? 1 : 0;
+  r->V = r->Hkv << r->vsh;
   r->total = r->cu[r->n_seq];
   r->sum_p = r->total - (int64_t)r->n_seq * r->W;
   return FKV_OK;
@@ -192,6 +195,7 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
   a.scores_tsp = scores_tsp;
   a.scores_head = scores_head;
   a.Hq = r.Hq; a.Hkv = r.Hkv; a.G = r.G; a.W = r.W;
+  a.V = r.V; a.vsh = r.vsh;
   const float scale = sh->softmax_scale > 0.f ? sh->softmax_scale : 1.0f / sqrtf((float)sh->head_dim);
   a.scale_log2e = scale * 1.4426950408889634f;
   a.causal = sh->causal;
@@ -208,7 +212,7 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
     const int halo = a.pool_r + (a.pool_r > r.W ? a.pool_r : r.W);
     int total = 0, clusters = 0;
     bool fits = false;
-    for (int n_sub = 1; n_sub * 32 <= fused_slots() && !fits && ctx->score_path != 1; ++n_sub) {
+    for (int n_sub = 1; n_sub * 32 <= fused_slots() && !fits && ctx->score_path != 1 && r.V <= kMaxKvHeads; ++n_sub) {
       const int cap_own = n_sub * 32 - halo;
       if (cap_own < 1) continue;
       fits = true;
@@ -283,7 +287,8 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
     int sub = scores_sub_short();
     const int64_t per_cu = (r.sum_p + n_cu - 1) / n_cu + 2 * a.pool_r;
     if (per_cu > (int64_t)sub * 32) sub = (int)((per_cu + 31) / 32);
-    if (sub > scores_sub_long()) sub = scores_sub_long();
+    const int sub_max = r.V > kMaxKvHeads ? scores_sub_wide() : scores_sub_long();
+    if (sub > sub_max) sub = sub_max;
     while (sub * 32 - 2 * a.pool_r < 1) ++sub;
     a.tile_sub = sub;
   }
@@ -658,6 +663,7 @@ int decode_common(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const voi
     a.n_pages = (int)pg->n_pages;
   }
   a.Hq = r.Hq; a.Hkv = r.Hkv; a.G = r.G; a.n_seq = r.n_seq;
+  a.V = r.V; a.vsh = r.vsh;
   int splits = (n_max + 63) / 64;  // at least 64 tokens per block, at most decode_max_splits() blocks per head
   if (splits < 1) splits = 1;
   if (splits > decode_max_splits()) splits = decode_max_splits();

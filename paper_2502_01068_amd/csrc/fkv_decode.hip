@@ -48,7 +48,7 @@ __device__ __forceinline__ void dec_merge(DecState &a, float m2, float l2, const
   a.m = mn;
 }
 
-// grid (n_split, Hkv, B); partial results part[((b*Hq + h)*n_split + s)*(128+2)]: 128 weighted sums, max, sum
+// grid (n_split, V, B), one block per split and virtual group; partial results part[((b*Hq + h)*n_split + s)*(128+2)]: 128 weighted sums, max, sum
 template <bool kPaged>
 __global__ __launch_bounds__(kDecThreads) void k_decode_partial(DecodeArgs a) {
   __shared__ float lds[kDecWaves][kMaxGroup][16][10];
@@ -59,12 +59,13 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_partial(DecodeArgs a) {
   int chunk = (n + a.n_split - 1) / a.n_split;
   chunk = (chunk + 15) / 16 * 16;
   const int t0 = s * chunk, t1 = min(n, t0 + chunk);
+  const int kvh = vg_kv_head(a, g), h0 = vg_head0(a, g), n_h = vg_heads(a, g);
 
   float qf[kMaxGroup][8];
 #pragma unroll
   for (int hl = 0; hl < kMaxGroup; ++hl) {
-    if (hl < a.G) {
-      const u32x4 w = *reinterpret_cast<const u32x4 *>(a.q + ((size_t)b * a.Hq + g * a.G + hl) * kHeadDim + c * 8);
+    if (hl < n_h) {
+      const u32x4 w = *reinterpret_cast<const u32x4 *>(a.q + ((size_t)b * a.Hq + h0 + hl) * kHeadDim + c * 8);
       unpack8(w, qf[hl]);
     } else {
 #pragma unroll
@@ -80,8 +81,8 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_partial(DecodeArgs a) {
     for (int i = 0; i < 8; ++i) st[hl].acc[i] = 0.f;
   }
   const size_t first = kPaged ? 0 : (size_t)a.off[b];  // a paged sequence is addressed through its block table
-  const uint16_t *kb = a.k + (size_t)g * a.head_stride + first * a.tok_stride + c * 8;
-  const uint16_t *vb = a.v + (size_t)g * a.head_stride + first * a.tok_stride + c * 8;
+  const uint16_t *kb = a.k + (size_t)kvh * a.head_stride + first * a.tok_stride + c * 8;
+  const uint16_t *vb = a.v + (size_t)kvh * a.head_stride + first * a.tok_stride + c * 8;
   const int32_t *table = kPaged ? a.block_table + (size_t)b * a.max_pages : nullptr;
 
   constexpr int kU = 4;  // token steps whose loads are in flight together
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_partial(DecodeArgs a) {
   if (wave == 0 && tq == 0) {
 #pragma unroll
     for (int hl = 0; hl < kMaxGroup; ++hl) {
-      if (hl >= a.G) continue;
+      if (hl >= n_h) continue;
       DecState r = st[hl];
       for (int w = 1; w < kDecWaves; ++w) {
         float acc2[8];
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_partial(DecodeArgs a) {
         for (int i = 0; i < 8; ++i) acc2[i] = lds[w][hl][c][i];
         dec_merge(r, lds[w][hl][c][8], lds[w][hl][c][9], acc2);
       }
-      float *dst = a.part + (((size_t)b * a.Hq + g * a.G + hl) * a.n_split + s) * (kHeadDim + 2);
+      float *dst = a.part + (((size_t)b * a.Hq + h0 + hl) * a.n_split + s) * (kHeadDim + 2);
 #pragma unroll
       for (int i = 0; i < 8; ++i) dst[c * 8 + i] = r.acc[i];
       if (c == 0) { dst[kHeadDim] = r.m; dst[kHeadDim + 1] = r.l; }
@@ -216,9 +217,9 @@ __global__ __launch_bounds__(4 * kHeadDim) void k_decode_combine(DecodeArgs a) {
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s) {
   if (a.block_table)
-    hipLaunchKernelGGL(k_decode_partial<true>, dim3(a.n_split, a.Hkv, a.n_seq), dim3(kDecThreads), 0, s, a);
+    hipLaunchKernelGGL(k_decode_partial<true>, dim3(a.n_split, a.V, a.n_seq), dim3(kDecThreads), 0, s, a);
   else
-    hipLaunchKernelGGL(k_decode_partial<false>, dim3(a.n_split, a.Hkv, a.n_seq), dim3(kDecThreads), 0, s, a);
+    hipLaunchKernelGGL(k_decode_partial<false>, dim3(a.n_split, a.V, a.n_seq), dim3(kDecThreads), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_decode_combine, dim3(a.Hq, a.n_seq), dim3(4 * kHeadDim), 0, s, a);

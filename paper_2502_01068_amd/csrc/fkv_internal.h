@@ -12,8 +12,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 128-bit load
 
 constexpr int kHeadDim = 128;     // d: one KV-head row is 256 bytes = 16 lanes x 16 B
 constexpr int kMaxWindow = 8;     // W <= 8: window index is the low 3 bits of an MFMA row
-constexpr int kMaxGroup = 4;      // G <= 4: head-in-group is the high 2 bits of an MFMA row
+constexpr int kMaxGroup = 4;      // query heads per MFMA row tile: head-in-tile is the high 2 bits of a row
 constexpr int kMaxKvHeads = 8;
+// A KV group of more than 4 query heads is processed as two "virtual groups" of up to 4 heads that
+// read the same K rows: virtual group v serves KV head v >> vsh and query heads
+// (v >> vsh) * G + (v & (vg - 1)) * 4 + {0..3} (those below G).  vg = 1 << vsh is 1 for G <= 4, else 2.
+constexpr int kMaxReal = 8;       // G <= 8
+constexpr int kMaxVGroups = 16;   // Hkv * vg
 constexpr int kRowsPerGroup = 32; // MFMA M: row m = head_in_group * 8 + w
 constexpr int kMaxPoolKernel = 31;
 
@@ -61,6 +66,7 @@ struct ScoreArgs {
   float *scores_tsp;      // [sum P] or nullptr
   SeqMap map;
   int Hq, Hkv, G, W;
+  int V, vsh;             // virtual groups (Hkv << vsh) and their shift, see kMaxVGroups
   float scale_log2e;      // softmax scale * log2(e)
   int causal;
   int pool_r;             // pooling radius (kernel = 2r+1)
@@ -88,6 +94,15 @@ struct FusedArgs {
   int own[FKV_MAX_SEQS];             // prefix tokens owned by each block of sequence b
   int cl0[FKV_MAX_SEQS + 1];         // first cluster of sequence b
 };
+// Virtual-group helpers (a = any args struct with Hkv, G, vsh).
+template <typename A> __host__ __device__ inline int vg_kv_head(const A &a, int v) { return v >> a.vsh; }
+template <typename A> __host__ __device__ inline int vg_head0(const A &a, int v) {
+  return (v >> a.vsh) * a.G + (v & ((1 << a.vsh) - 1)) * kMaxGroup;
+}
+template <typename A> __host__ __device__ inline int vg_heads(const A &a, int v) {
+  const int left = a.G - (v & ((1 << a.vsh) - 1)) * kMaxGroup;
+  return left < kMaxGroup ? left : kMaxGroup;
+}
 int fused_slots(void);
 int fused_cluster_size(void);
 int score_fused_max_blocks_per_cu(void);
@@ -96,6 +111,7 @@ hipError_t launch_score_fused(const ScoreArgs &a, const FusedArgs &f, hipStream_
 int stats_chunk_tokens(void);
 int scores_sub_short(void);
 int scores_sub_long(void);
+int scores_sub_wide(void);
 hipError_t launch_stats(const ScoreArgs &a, int n_blocks, hipStream_t s);
 hipError_t launch_combine(const ScoreArgs &a, hipStream_t s);
 hipError_t launch_scores(const ScoreArgs &a, int n_blocks, hipStream_t s);
@@ -137,6 +153,7 @@ struct DecodeArgs {
   float *part;           // [B][Hq][n_split][d + 2]
   int64_t tok_stride, head_stride;
   int Hq, Hkv, G, n_split, n_seq;
+  int V, vsh;            // virtual groups, as in ScoreArgs
   float scale_log2e;
   int off[FKV_MAX_SEQS + 1];
   // paged cache (block_table != nullptr): k, v are page pools [n_pages][page_size][Hkv][d]; logical

@@ -24,6 +24,7 @@ namespace fkv {
 int stats_chunk_tokens(void) { return kStatsChunk; }
 int scores_sub_short(void) { return kScoresSubShort; }
 int scores_sub_long(void) { return kScoresSubLong; }
+int scores_sub_wide(void) { return kScoresSubWide; }
 
 __global__ __launch_bounds__(kThreads) void k_stats(ScoreArgs a) {
   __shared__ __attribute__((aligned(16))) uint8_t stage_all[kWaves * kStageBytes];
@@ -39,7 +40,7 @@ __global__ __launch_bounds__(kThreads) void k_stats(ScoreArgs a) {
   uint8_t *stage = stage_all + wave * kStageBytes;
 
   FKV_TICK(16);
-  for (int g = wave; g < a.Hkv; g += kWaves) {
+  for (int g = wave; g < a.V; g += kWaves) {
     bf16x8 qa[8];
     load_q(a, b, g, lane, qa);
     float mx[16], sm[16];
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void k_stats(ScoreArgs a) {
 __global__ __launch_bounds__(256) void k_combine(ScoreArgs a) {
   const int lane = threadIdx.x & 63;
   const int rid = blockIdx.x * 4 + (threadIdx.x >> 6);  // (b, g, m)
-  const int rows_per_seq = a.Hkv * kRowsPerGroup;
+  const int rows_per_seq = a.V * kRowsPerGroup;
   if (rid >= a.map.n_seq * rows_per_seq) return;
   const int b = rid / rows_per_seq, gm = rid - b * rows_per_seq;
   const int p0 = a.map.blk[b], p1 = a.map.blk[b + 1];
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(256) void k_combine(ScoreArgs a) {
   for (int off = 1; off < 64; off <<= 1) S += __shfl_xor(S, off);
   if (lane == 0) {
     const int row = gm & 31;
-    const bool ok = (row >> 3) < a.G && (row & 7) < a.W;
+    const bool ok = (row >> 3) < vg_heads(a, gm >> 5) && (row & 7) < a.W;
     // probability = exp2(z*scale*log2e - (Mx + log2 S))
     a.rowstat[(size_t)b * rows_per_seq + gm] = ok ? (Mx + __log2f(S)) : 0.f;
   }
@@ -103,12 +104,12 @@ __global__ __launch_bounds__(256) void k_combine(ScoreArgs a) {
 // kMaxSub 32-token sub-tiles per block at most; a.tile_sub of them are used (host-chosen so that
 // the launch is about one block per CU).  The window sums go straight into their own LDS array,
 // next to the waves' staging tiles.
-template <int kMaxSub>
+template <int kMaxSub, int kGroups>
 __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
   constexpr int kSlots = kMaxSub * kSub;
   __shared__ __attribute__((aligned(16))) uint8_t stage_all[kWaves * kStageBytes];
-  __shared__ float s_head[kMaxKvHeads * kMaxGroup][kSlots];  // window-summed probabilities per head
-  __shared__ float g_sum[kMaxKvHeads][kSlots];               // per-group sums of pooled head scores
+  __shared__ float s_head[kGroups * kMaxGroup][kSlots];  // window-summed probabilities per head
+  __shared__ float g_sum[kGroups][kSlots];               // per virtual group sums of pooled head scores
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 31, hi = lane >> 5;
@@ -123,11 +124,11 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
   uint8_t *stage = stage_all + wave * kStageBytes;
 
   FKV_TICK(24);
-  for (int g = wave; g < a.Hkv; g += kWaves) {
+  for (int g = wave; g < a.V; g += kWaves) {
     bf16x8 qa[8];
     load_q(a, b, g, lane, qa);
     float cst[16];
-    const float *rs = a.rowstat + ((size_t)b * a.Hkv + g) * kRowsPerGroup;
+    const float *rs = a.rowstat + ((size_t)b * a.V + g) * kRowsPerGroup;
 #pragma unroll
     for (int q = 0; q < 16; ++q) cst[q] = rs[(q >> 2) * 8 + hi * 4 + (q & 3)];
 
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
           sum += (hi * 4 + rr < a.W) ? e : 0.f;
         }
         sum = add_across_halves(sum);  // other half of the window rows
-        if (hi == 0 && hl < a.G) s_head[g * kMaxGroup + hl][st * kSub + n] = inb ? sum : 0.f;
+        if (hi == 0 && hl < vg_heads(a, g)) s_head[g * kMaxGroup + hl][st * kSub + n] = inb ? sum : 0.f;
       }
     });
   }
@@ -161,15 +162,17 @@ hipError_t launch_stats(const ScoreArgs &a, int n_blocks, hipStream_t s) {
   return hipGetLastError();
 }
 hipError_t launch_combine(const ScoreArgs &a, hipStream_t s) {
-  const int rows = a.map.n_seq * a.Hkv * kRowsPerGroup;
+  const int rows = a.map.n_seq * a.V * kRowsPerGroup;
   hipLaunchKernelGGL(k_combine, dim3((rows + 3) / 4), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_scores(const ScoreArgs &a, int n_blocks, hipStream_t s) {
-  if (a.tile_sub <= kScoresSubShort)
-    hipLaunchKernelGGL(k_scores<kScoresSubShort>, dim3(n_blocks), dim3(kThreads), 0, s, a);
+  if (a.V > kMaxKvHeads)  // twice the heads in LDS: half the tile
+    hipLaunchKernelGGL((k_scores<kScoresSubWide, kMaxVGroups>), dim3(n_blocks), dim3(kThreads), 0, s, a);
+  else if (a.tile_sub <= kScoresSubShort)
+    hipLaunchKernelGGL((k_scores<kScoresSubShort, kMaxKvHeads>), dim3(n_blocks), dim3(kThreads), 0, s, a);
   else
-    hipLaunchKernelGGL(k_scores<kScoresSubLong>, dim3(n_blocks), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((k_scores<kScoresSubLong, kMaxKvHeads>), dim3(n_blocks), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 

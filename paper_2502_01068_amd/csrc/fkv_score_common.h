@@ -13,6 +13,7 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kStatsChunk = 128;     // fewest tokens per block in k_stats
 constexpr int kScoresSubShort = 4;   // k_scores: sub-tiles per block (incl. pooling halo), short inputs
 constexpr int kScoresSubLong = 18;   // ... and the most for long inputs (LDS bound)
+constexpr int kScoresSubWide = 9;    // ... when more than 8 virtual groups keep their window sums in LDS
 constexpr int kSub = 32;             // tokens per MFMA sub-tile
 constexpr int kStageBytes = kSub * kHeadDim * 2;  // 8 KiB per wave
 constexpr float kNegBig = -1.0e30f;
@@ -32,15 +33,15 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// MFMA A operand for KV group g: lane (m = lane%32, hi = lane/32) holds, for step s, the 8
-// values d = hi*64 + s*8 .. +7 of query row m (head g*G + m/8, window row m%8).  The
+// MFMA A operand for virtual group g: lane (m = lane%32, hi = lane/32) holds, for step s, the 8
+// values d = hi*64 + s*8 .. +7 of query row m (head vg_head0(g) + m/8, window row m%8).  The
 // contraction index may be permuted freely as long as K uses the same permutation.
 __device__ __forceinline__ void load_q(const ScoreArgs &a, int b, int g, int lane, bf16x8 (&qa)[8]) {
   const int m = lane & 31, hi = lane >> 5;
   const int hl = m >> 3, w = m & 7;
-  const bool ok = hl < a.G && w < a.W;
+  const bool ok = hl < vg_heads(a, g) && w < a.W;
   const u32x4 *src = reinterpret_cast<const u32x4 *>(
-      a.q_win + (((size_t)b * a.W + (ok ? w : 0)) * a.Hq + (size_t)g * a.G + (ok ? hl : 0)) * kHeadDim + hi * 64);
+      a.q_win + (((size_t)b * a.W + (ok ? w : 0)) * a.Hq + (size_t)vg_head0(a, g) + (ok ? hl : 0)) * kHeadDim + hi * 64);
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
     u32x4 v = src[s];
@@ -49,7 +50,7 @@ __device__ __forceinline__ void load_q(const ScoreArgs &a, int b, int g, int lan
   }
 }
 
-// Streams the K rows of one KV head for `n_sub` consecutive 32-token sub-tiles starting at
+// Streams the K rows of virtual group g's KV head for `n_sub` consecutive 32-token sub-tiles starting at
 // sequence-local token `first` (tokens are clamped into [0, Lb-1] for the load; the caller masks
 // what lies outside its range).  fn(st, acc) receives the raw logits of sub-tile st:
 // acc[r] = q_row(m) . k(token first + st*32 + lane%32) with m = (r/4)*8 + (lane/32)*4 + r%4,
@@ -62,7 +63,7 @@ __device__ __forceinline__ void stream_head(const ScoreArgs &a, const bf16x8 (&q
   const int c = lane & 15;        // 16-byte column of the 256-byte head row
   const int tq = lane >> 4;       // token within a quad of 4 tokens per load instruction
   const int n = lane & 31, hi = lane >> 5;
-  const uint16_t *kbase = a.k + (size_t)g * kHeadDim + c * 8;
+  const uint16_t *kbase = a.k + (size_t)vg_kv_head(a, g) * kHeadDim + c * 8;
   const size_t tok_stride = (size_t)a.Hkv * kHeadDim;
 
   u32x4 nxt[8];
@@ -146,7 +147,7 @@ __device__ __forceinline__ float2 merge_stats(float2 x, float2 y) {
 
 // Pools the per-head window sums along tokens (Eq. 1), averages the heads of each KV group
 // (App. B.1) and all heads (Eq. 2) and writes the scores of the owned tokens [o0, o1).
-// s_head[h][slot] holds head h's window-summed probability of token j0 + slot, 0 outside the
+// s_head[4 v + i][slot] holds the window-summed probability of head i of virtual group v at token j0 + slot, 0 outside the
 // prefix: neutral for max pooling (scores are >= 0) and the zero padding of avg pooling.
 // Slots o0 - r - j0 .. o1 + r - 1 - j0 must be filled.  Contains block barriers.
 template <int kStride>
@@ -157,13 +158,15 @@ __device__ __forceinline__ void pool_and_write(const ScoreArgs &a, const float (
   const float inv_k = 1.0f / (float)(2 * r + 1), inv_g = 1.0f / (float)a.G, inv_h = 1.0f / (float)a.Hq;
   const bool is_max = a.pool_mode == FKV_POOL_MAX;
   const int lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
-  for (int g = threadIdx.x >> 6; g < a.Hkv; g += n_waves) {  // one wave per KV group
+  const bool split = a.vsh != 0;  // a KV group spans two virtual groups: its mean is formed after the barrier
+  for (int g = threadIdx.x >> 6; g < a.V; g += n_waves) {  // one wave per virtual group
+    const int n_h = vg_heads(a, g), h0 = vg_head0(a, g);
 #pragma unroll 1
     for (int jj = lane; jj < own; jj += 64) {
       const int c = o0 + jj - j0;  // slot of the pooled token
       float gs = 0.f;
 #pragma unroll 1
-      for (int hl = 0; hl < a.G; ++hl) {
+      for (int hl = 0; hl < n_h; ++hl) {
         const float *row = s_head[g * kMaxGroup + hl] + c;
         float p;
         if (r == 3) {
@@ -178,18 +181,25 @@ __device__ __forceinline__ void pool_and_write(const ScoreArgs &a, const float (
           for (int t = -r; t <= r; ++t) p += row[t];
           p *= inv_k;
         }
-        if (a.scores_head) a.scores_head[(size_t)(g * a.G + hl) * a.sum_p + col0 + o0 + jj] = p;
+        if (a.scores_head) a.scores_head[(size_t)(h0 + hl) * a.sum_p + col0 + o0 + jj] = p;
         gs += p;
       }
       g_sum[g][jj] = gs;
-      if (a.scores_group) a.scores_group[(size_t)g * a.sum_p + col0 + o0 + jj] = gs * inv_g;
+      if (a.scores_group && !split) a.scores_group[(size_t)g * a.sum_p + col0 + o0 + jj] = gs * inv_g;
+    }
+  }
+  if (a.scores_tsp == nullptr && !(split && a.scores_group)) return;
+  __syncthreads();
+  if (split && a.scores_group) {
+    for (int i = threadIdx.x; i < own * a.Hkv; i += blockDim.x) {
+      const int kv = i / own, jj = i - kv * own;
+      a.scores_group[(size_t)kv * a.sum_p + col0 + o0 + jj] = (g_sum[2 * kv][jj] + g_sum[2 * kv + 1][jj]) * inv_g;
     }
   }
   if (a.scores_tsp == nullptr) return;
-  __syncthreads();
   for (int jj = threadIdx.x; jj < own; jj += blockDim.x) {
     float tot = 0.f;
-    for (int g = 0; g < a.Hkv; ++g) tot += g_sum[g][jj];
+    for (int g = 0; g < a.V; ++g) tot += g_sum[g][jj];
     a.scores_tsp[col0 + o0 + jj] = tot * inv_h;
   }
 }

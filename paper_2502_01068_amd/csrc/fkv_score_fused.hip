@@ -82,7 +82,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   const int n_sub = (c1 - c0 + kSub - 1) / kSub;                // <= kFusedSub (host guarantees)
   uint8_t *stage = lds_all + wave * kStageBytes;
   const int g = wave;
-  const bool has_group = g < a.Hkv;
+  const bool has_group = g < a.V;  // the host takes this kernel only for V <= 8 (one wave per virtual group)
 
   FKV_TICK(32);
   FKV_BTICK(0);
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   }
   __syncthreads();
   if (flag_lds[0]) {  // this block closes its cluster
-    if ((int)threadIdx.x < a.Hkv * kRowsPerGroup) {
+    if ((int)threadIdx.x < a.V * kRowsPerGroup) {
       const float2 *src = f.bpartial + (size_t)threadIdx.x * f.bpartial_stride + cl_first;
       float2 v[kClusterSize];  // all loads in flight before the (ordered) fold
 #pragma unroll
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
     oth.y = __shfl_xor(acc.y, 32);
     const float2 lo2 = half ? oth : acc, hi2 = half ? acc : oth;
     const float2 tot = merge_stats(lo2, hi2);
-    const bool row_ok = (row >> 3) < a.G && (row & 7) < a.W;
+    const bool row_ok = (row >> 3) < vg_heads(a, g) && (row & 7) < a.W;
     if (lane < 32) cst_lds[wave][row] = row_ok ? (tot.x + __log2f(tot.y)) : 0.f;
   }
   __syncthreads();  // all staging tiles are dead, cst_lds is visible
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) sum += (hi * 4 + rr < a.W) ? z[st][hl * 4 + rr] * fac[hl * 4 + rr] : 0.f;
           sum = add_across_halves(sum);  // other half of the window rows
-          if (hi == 0 && hl < a.G) s_head[g * kMaxGroup + hl][st * kSub + n] = inb ? sum : 0.f;
+          if (hi == 0 && hl < vg_heads(a, g)) s_head[g * kMaxGroup + hl][st * kSub + n] = inb ? sum : 0.f;
         }
       }
     }

@@ -50,6 +50,8 @@ def test_check_shape_accepts_paper_configs(lib):
     assert lib.fkv_check_shape(ctypes.byref(_shape(lengths=[8192, 16384, 9000], pool_mode="avg"))) == fk.FKV_OK
     assert lib.fkv_check_shape(ctypes.byref(_shape(lengths=8))) == fk.FKV_OK  # L == W: empty prefix
     assert lib.fkv_check_shape(ctypes.byref(_shape(n_q_heads=8, n_kv_heads=8, window=4, pool_kernel=1))) == fk.FKV_OK
+    assert lib.fkv_check_shape(ctypes.byref(_shape(n_q_heads=64, n_kv_heads=8))) == fk.FKV_OK   # G = 8
+    assert lib.fkv_check_shape(ctypes.byref(_shape(n_q_heads=28, n_kv_heads=4))) == fk.FKV_OK   # G = 7
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -63,7 +65,7 @@ def test_check_shape_accepts_paper_configs(lib):
     (dict(softmax_scale=float("nan")), fk.FKV_EINVAL),
     (dict(head_dim=64), fk.FKV_EUNSUPPORTED),
     (dict(window=16), fk.FKV_EUNSUPPORTED),
-    (dict(n_q_heads=64), fk.FKV_EUNSUPPORTED),              # G = 8
+    (dict(n_q_heads=72), fk.FKV_EUNSUPPORTED),              # G = 9
     (dict(n_q_heads=32, n_kv_heads=16), fk.FKV_EUNSUPPORTED),
     (dict(pool_kernel=33), fk.FKV_EUNSUPPORTED),
     (dict(lengths=[64] * 65), fk.FKV_EUNSUPPORTED),

@@ -30,7 +30,7 @@ def ctx():
 
 @pytest.mark.parametrize("ns,Hq,Hkv,scale", [
     ([1], 32, 8, 0.0), ([17], 32, 8, 0.0), ([128], 32, 8, 0.0), ([129], 32, 8, 0.0), ([2048], 32, 8, 0.0),
-    ([5000], 32, 8, 0.0), ([300, 1, 2049, 64], 32, 8, 0.0), ([777], 8, 8, 0.25), ([513, 90], 12, 4, 0.0),
+    ([5000], 32, 8, 0.0), ([300, 1, 2049, 64], 32, 8, 0.0), ([777], 8, 8, 0.25), ([513, 90], 12, 4, 0.0), ([1500], 64, 8, 0.0), ([333, 70], 28, 4, 0.0),
 ])
 @pytest.mark.parametrize("layout", ["compact", "token_major"])
 def test_decode_attention_parity(ctx, ns, Hq, Hkv, scale, layout):

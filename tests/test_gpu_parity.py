@@ -62,6 +62,11 @@ def test_scores_config1(ctx, pool_mode):
     (513, 16, 8, 8, 31, True, 0.0),     # widest supported pooling kernel
     (1267, 3, 3, 4, 27, True, 0.0),     # pooling radius beyond the window: the halo of the last tokens runs past L
     (200, 4, 4, 1, 31, True, 0.0),      # ... with a one-token window
+    (900, 64, 8, 8, 7, True, 0.0),      # G = 8: two row tiles per KV head, 16 virtual groups (two-pass kernels only)
+    (700, 32, 4, 8, 7, True, 0.0),      # G = 8 with 4 KV heads: fits the single-pass kernel
+    (650, 28, 4, 8, 7, True, 0.0),      # G = 7: the second row tile has 3 heads
+    (400, 5, 1, 3, 5, False, 0.0),      # G = 5, one KV head
+    (1300, 48, 8, 8, 7, True, 0.0),     # G = 6
 ])
 @pytest.mark.parametrize("pool_mode", ["max", "avg"])
 def test_scores_shapes(ctx, L, Hq, Hkv, W, pk, causal, scale, pool_mode):
@@ -351,6 +356,40 @@ def test_per_head_retention(ctx, pool_mode):
         o += budget[b]
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(64, 8), (28, 4), (40, 8)])
+def test_wide_groups_pipeline(ctx, Hq, Hkv):
+    """Groups of more than 4 query heads (two MFMA row tiles per KV head): fused call, head-wise scores and
+    head-wise gather against the oracle."""
+    L, W, budget, k_tsp = 1800, 8, 200, 360
+    G = Hq // Hkv
+    print("case: wide groups Hq=%d Hkv=%d" % (Hq, Hkv), flush=True)
+    s = wl.make_sequence(17, L, n_q_heads=Hq, n_kv_heads=Hkv, n_heavy=10, hidden=256)
+    shape = fk.make_shape(L, n_q_heads=Hq, n_kv_heads=Hkv, pool_mode="max")
+    q, k, v, x = (dev_bf16(s[n]) for n in ("q_win", "k", "v", "x"))
+    out = ctx.fkv_compress_kv(shape, q[None], k, v, budget, x=x, k_tsp_per_seq=k_tsp)
+    sg, st = ctx.fkv_score_window(shape, q[None], k)
+    sh = ctx.fkv_score_heads(shape, q[None], k)
+    ref = oracle.compress_kv(s["q_win"], s["k"], s["v"], budget, 7, "max", x=s["x"], k_tsp=k_tsp)
+    sc = oracle.score_window(s["q_win"], s["k"], 7, "max", precision="f64")
+    assert_scores_close(sg.cpu().numpy(), sc["scores_group"], "scores_group")
+    assert_scores_close(st.cpu().numpy(), sc["scores_tsp"], "scores_tsp")
+    assert_scores_close(sh.cpu().numpy(), sc["p_head"], "scores_head")
+    idx_kv, idx_tsp = out["idx_kv"].cpu().numpy(), out["idx_tsp"].cpu().numpy()
+    for g in range(Hkv):
+        assert_index_set(idx_kv[g], ref["idx_kv"][g], ref["scores_group"][g], W, "kv g%d" % g)
+        np.testing.assert_array_equal(host_bits(out["k_out"][g]), s["k"][idx_kv[g], g])
+        np.testing.assert_array_equal(host_bits(out["v_out"][g]), s["v"][idx_kv[g], g])
+    assert_index_set(idx_tsp, ref["idx_tsp"], ref["scores_tsp"], W, "tsp")
+    np.testing.assert_array_equal(host_bits(out["x_out"]), s["x"][idx_tsp])
+    idx_h = ctx.fkv_select_topk(shape, sh, budget)
+    ko, vo = ctx.fkv_gather_kv_per_head(shape, k, v, idx_h, budget)
+    idx_hh = idx_h.cpu().numpy()
+    np.testing.assert_array_equal(host_bits(ko), oracle.gather_kv_per_head(s["k"], idx_hh))
+    np.testing.assert_array_equal(host_bits(vo), oracle.gather_kv_per_head(s["v"], idx_hh))
+    for h in (0, G - 1, G, Hq - 1):
+        np.testing.assert_array_equal(idx_hh[h], oracle.select_topk(sh[h].cpu().numpy(), W, budget))
+
+
 def test_deterministic(ctx):
     print("case: determinism", flush=True)
     s = wl.make_sequence(4, 3000, n_heavy=30)
@@ -456,7 +495,7 @@ def test_random_valid_shapes(ctx, case):
     """Seeded random draws over everything the boundary accepts: head counts, window, pooling kernel and
     mode, mask, scale, ragged batches, keep counts; score -> select -> K/V gather against the oracle."""
     rng = np.random.default_rng(1000 + case)
-    Hkv, G, W = int(rng.integers(1, 9)), int(rng.integers(1, 5)), int(rng.integers(1, 9))
+    Hkv, G, W = int(rng.integers(1, 9)), int(rng.integers(1, 9)), int(rng.integers(1, 9))
     Hq = Hkv * G
     pk = int(rng.integers(0, 16)) * 2 + 1
     causal, pool_mode = bool(rng.integers(0, 2)), ("max", "avg")[int(rng.integers(0, 2))]

@@ -111,7 +111,7 @@ def test_random_fused_call_equals_its_steps(ctx, case):
 @pytest.mark.parametrize("case", range(12))
 def test_random_decode(ctx, case):
     rng = np.random.default_rng(6000 + case)
-    Hkv, G = int(rng.integers(1, 9)), int(rng.integers(1, 5))
+    Hkv, G = int(rng.integers(1, 9)), int(rng.integers(1, 9))
     Hq, d = Hkv * G, 128
     B = int(rng.integers(1, 5))
     ns = [int(rng.integers(1, 5000)) for _ in range(B)]
