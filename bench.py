@@ -178,6 +178,8 @@ def main():
     ap.add_argument("--workload", default="config2_L32768", choices=sorted(WORKLOADS) + ["config5_chain", "decode"])
     ap.add_argument("--pool", default="avg", choices=["avg", "max"])
     ap.add_argument("--pool-kernel", type=int, default=7, help="odd pooling kernel size (the paper uses 7)")
+    ap.add_argument("--tsp-rate", type=float, default=None, help="override the workload's TSP keep count with round-half-up(rate * L)")
+    ap.add_argument("--kv-rate", type=float, default=None, help="override the workload's KV budget with round-half-up(rate * L)")
     ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated over the steps")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -204,6 +206,10 @@ def main():
 
     L, k_tsp, budget = WORKLOADS[args.workload]
     W = 8
+    if args.tsp_rate is not None:
+        k_tsp = max(W, wl.round_half_up(args.tsp_rate * L))
+    if args.kv_rate is not None:
+        budget = max(W, wl.round_half_up(args.kv_rate * L))
     torch.cuda.set_device(0)
     ctx = fk.Context(max_total_tokens=L, max_seqs=1, device=0)
     shape = fk.make_shape(L, pool_mode=args.pool, pool_kernel=args.pool_kernel)
