@@ -125,7 +125,7 @@ struct SelectRowSet {
   int cnt_off[FKV_MAX_SEQS + 1];  // prefix sums of the per-sequence keep counts
 };
 // Rows longer than 32768 keys are selected by a chain of launches that keeps per-row state here.
-constexpr int kLongMaxInst = 64;     // (row, sequence) instances one call may have on that path
+constexpr int kLongMaxInst = 256;    // (row, sequence) instances one call may have on that path (8.4 MB of state)
 constexpr int kLongMaxSlices = 1024; // 8192-key slices per row (8.4M keys)
 constexpr int kLongInfo = 3 * 2048;  // words: [3][2048] histograms, 16 info words, 2 counts per slice
 constexpr int kLongCnt = kLongInfo + 16;

@@ -145,7 +145,8 @@ def test_select_bit_exact(ctx, P, ks, ties):
 
 @pytest.mark.parametrize("P,rows,ks", [
     (1000003, 2, [8, 4096, 200001]),     # 123 slices of the multi-block chain
-    (40000, 66, [8008]),                 # more row instances than the chain's state holds: one-block chunked kernel
+    (40000, 66, [8008]),                 # many rows on the multi-block chain
+    (33000, 260, [3000]),                # more row instances than the chain's state holds: one-block chunked kernel
     (32766, 1, [6554]), (32767, 2, [6554]),  # either side of the register-resident limit
 ])
 def test_select_long_rows(P, rows, ks):
