@@ -158,3 +158,37 @@ def test_config2_repeatability_under_load():
     finally:
         for c in ctxs:
             c.close()
+
+
+def test_config5_chain_32_layers():
+    """The whole selection chain of Algorithm 1 at the benchmark's size: layers 0-15 on 32768 tokens
+    (layer 15 also propagates 6554 hidden rows), layers 16-31 on 6554 tokens, independent seeded inputs
+    per layer, one context reused as bench.py does.  Every layer's outputs are checked against the oracle."""
+    L, n_layers, tsp_layer = 32768, 32, 15
+    ctx = fk.Context(max_total_tokens=L, max_seqs=1)
+    tokens = 0
+    try:
+        for layer in range(n_layers):
+            Lc, k_tsp, budget = fk.fkv_plan_layer(layer, n_layers, tsp_layer, L, 0.2, 2048 / L)
+            tokens += Lc
+            print("  layer %d: %d tokens, k_tsp %d, budget %d" % (layer, Lc, k_tsp, budget), flush=True)
+            s = wl.make_sequence(3, Lc, layer=layer, with_x=(k_tsp > 0))
+            shape = fk.make_shape(Lc, pool_mode="avg")
+            q, k, v = dev_bf16(s["q_win"]), dev_bf16(s["k"]), dev_bf16(s["v"])
+            x = dev_bf16(s["x"]) if k_tsp else None
+            out = ctx.fkv_compress_kv(shape, q, k, v, budget, x=x, k_tsp_per_seq=(k_tsp or None))
+            ref = oracle.compress_kv(s["q_win"], s["k"], s["v"], budget, 7, "avg", x=s.get("x") if k_tsp else None,
+                                     k_tsp=(k_tsp or None))
+            idx_kv = out["idx_kv"].cpu().numpy()
+            for g in range(8):
+                assert_index_set(idx_kv[g], ref["idx_kv"][g], ref["scores_group"][g], W, "layer %d kv g%d" % (layer, g))
+                np.testing.assert_array_equal(host_bits(out["k_out"][g]), s["k"][idx_kv[g], g])
+                np.testing.assert_array_equal(host_bits(out["v_out"][g]), s["v"][idx_kv[g], g])
+            if k_tsp:
+                idx_tsp = out["idx_tsp"].cpu().numpy()
+                assert_index_set(idx_tsp, ref["idx_tsp"], ref["scores_tsp"], W, "layer %d tsp" % layer)
+                np.testing.assert_array_equal(host_bits(out["x_out"]), s["x"][idx_tsp])
+        assert tokens == 16 * 32768 + 16 * 6554      # the 60 % prefill compute rate of Sec. 5.1
+        assert ctx.fkv_query_error() == 0
+    finally:
+        ctx.close()
