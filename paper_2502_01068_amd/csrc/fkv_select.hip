@@ -30,6 +30,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   const int n_chunks = kResident ? 1 : (P + mis + kChunk - 1) / kChunk;
   uint32_t key[kKpt];
   FKV_TICK(0);
+  FKV_BTICK(0);
 
   // ---- key range of the row: the radix digits are taken relative to the smallest key, so
   // the bins spread over the values the row really holds instead of over fp32's exponent
@@ -53,6 +54,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   kmin += 1u;
 
   FKV_TICK(1);
+  FKV_BTICK(1);
   // ---- narrow [lo, lo + 2^s) down to the key T of the kp-th largest score
   uint32_t lo = kmin, remaining = (uint32_t)kp, need_eq = remaining;
   int s = (kmax == kmin) ? 0 : 32 - __clz(kmax - kmin);  // kmax - kmin < 2^s
@@ -150,6 +152,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   // bin is kept, T is the smallest key the bin could hold and every key == T is kept.
   const uint32_t T = lo;
   FKV_TICK(2);
+  FKV_BTICK(2);
 
   // ---- ordered compaction.  Index order inside a wave is (q, lane, e).
   uint32_t run_gt = 0, run_eq = 0;
@@ -158,6 +161,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
     compact_chunk<kKpt>(key, T, need_eq, run_gt, run_eq, ch * kChunk - mis, out, scan_tbl, wsum, bcast + 8);
   }
   FKV_TICK(3);
+  FKV_BTICK(3);
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
