@@ -57,13 +57,15 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   FKV_BTICK(1);
   // ---- narrow [lo, lo + 2^s) down to the key T of the kp-th largest score
   uint32_t lo = kmin, remaining = (uint32_t)kp, need_eq = remaining;
+  uint32_t n_in = (uint32_t)P;  // keys in the current interval [lo, lo + 2^s)
   int s = (kmax == kmin) ? 0 : 32 - __clz(kmax - kmin);  // kmax - kmin < 2^s
   bool whole_bin = false;
 
   // Picks the histogram bin that holds the `remaining`-th largest candidate and narrows the
   // interval to it.  Expects hist filled and a barrier passed; leaves a barrier behind.
   auto narrow = [&](int shift) {
-    const BinPick p = pick_bin(hist, wsum, bcast, remaining);
+    const BinPick p = pick_bin(hist, wsum, bcast, remaining, n_in);
+    n_in = p.in_bin;
     lo += p.digit << shift;
     remaining = p.remaining;
     need_eq = remaining;
@@ -85,9 +87,14 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
     clear_hist();
     for (int ch = 0; ch < n_chunks; ++ch) {
       if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
+      const uint32_t span = s >= 32 ? 0xFFFFFFFFu : ((1u << s) - 1u);
 #pragma unroll
-      for (int e = 0; e < kKpt; ++e)  // branch-free: empty slots (key 0) count into a spare word per lane
-        atomicAdd(&hist[key[e] ? (key[e] - lo) >> shift : (uint32_t)kBins + (lane & 31)], 1u);
+      for (int e = 0; e < kKpt; ++e) {
+        // branch-free: what is not counted goes to a spare word per bank.  Not counted: empty slots (key 0)
+        // and the keys equal to lo, whose number pick_bin recovers from the histogram's total
+        const uint32_t rel = key[e] - lo;
+        atomicAdd(&hist[(key[e] > lo && rel <= span) ? rel >> shift : (uint32_t)kBins + (lane & 31)], 1u);
+      }
     }
     __syncthreads();
     FKV_TICK(8);
@@ -137,9 +144,9 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
       for (int ch = 0; ch < n_chunks; ++ch) {
         if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
 #pragma unroll
-        for (int e = 0; e < kKpt; ++e) {
+        for (int e = 0; e < kKpt; ++e) {  // keys equal to lo are left to pick_bin's total, as in round 1
           const uint32_t rel = key[e] - lo;
-          if (key[e] >= lo && rel <= span) atomicAdd(&hist[rel >> shift], 1u);
+          atomicAdd(&hist[(key[e] > lo && rel <= span) ? rel >> shift : (uint32_t)kBins + (lane & 31)], 1u);
         }
       }
       __syncthreads();
@@ -165,8 +172,8 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
-  __shared__ uint32_t hist[kBins + 32];  // + spare words for empty key slots (never read; one per bank, so a
-                                         // short row's many empty slots do not pile onto one address)
+  __shared__ uint32_t hist[kBins + 32];  // + spare words for key slots that are not counted (never read; one
+                                         // per bank, so they do not pile onto one address)
   __shared__ __attribute__((aligned(16))) uint32_t scan_tbl[kSelWaves * 64 * kMaxKpt];  // 128 KiB: scan tables / output staging
   __shared__ uint32_t wsum[2 * kSelWaves];
   __shared__ uint32_t bcast[8 + 64];  // broadcast slots, then one sink word per lane

@@ -67,18 +67,30 @@ struct BinPick {
 
 // Expects hist[0..kBins) filled and a block barrier passed; every thread gets the same result and a
 // barrier is left behind.  wsum: kSelWaves words, bcast: 4 words of LDS.
-__device__ __forceinline__ BinPick pick_bin(const uint32_t *hist, uint32_t *wsum, uint32_t *bcast, uint32_t remaining) {
+// n_total: number of keys in the interval the histogram covers, or kNoDeficit.  A fill may leave out
+// the keys equal to the interval's lower end (they all fall into bin 0): what is missing from the
+// histogram's total is credited to bin 0 here.  Mass ties sit at the smallest key in practice (scores
+// that underflowed to zero), and thousands of atomics on one LDS word would serialise.
+constexpr uint32_t kNoDeficit = 0xFFFFFFFFu;
+__device__ __forceinline__ BinPick pick_bin(const uint32_t *hist, uint32_t *wsum, uint32_t *bcast, uint32_t remaining,
+                                            uint32_t n_total = kNoDeficit) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // thread t owns the bin pair 2*(1023-t), 2*(1023-t)+1: thread order runs from the top bin down, so
   // an inclusive prefix sum over threads counts the candidates in this pair and above it
   const int pair = kSelThreads - 1 - tid;
-  const uint32_t h0 = hist[2 * pair], h1 = hist[2 * pair + 1];
-  const uint32_t mine = h0 + h1;
+  uint32_t h0 = hist[2 * pair];
+  const uint32_t h1 = hist[2 * pair + 1];
+  uint32_t mine = h0 + h1;
   const uint32_t run = wave_scan_add(mine);
   if (lane == 63) wsum[wave] = run;
   __syncthreads();
   uint32_t above = run - mine;
   for (int w = 0; w < wave; ++w) above += wsum[w];
+  if (pair == 0 && n_total != kNoDeficit) {  // the last thread in scan order sees the histogram's total
+    const uint32_t deficit = n_total - (above + mine);
+    h0 += deficit;
+    mine += deficit;
+  }
   if (above < remaining && remaining <= above + mine) {
     const bool top = remaining <= above + h1;
     bcast[0] = 2 * pair + (top ? 1 : 0);

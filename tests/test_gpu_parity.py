@@ -184,6 +184,27 @@ def test_select_negative_and_zero_scores(ctx):
             np.testing.assert_array_equal(idx[r], oracle.select_topk(scores[r], W, k))
 
 
+@pytest.mark.parametrize("P", [3000, 20000, 32760, 50000])
+def test_select_rows_with_mass_ties_at_the_minimum(ctx, P):
+    """Most of a row at its smallest value (probabilities that underflowed to zero): those keys are not
+    histogrammed one by one, their count is recovered from the histogram's total."""
+    print("case: select with mass ties at the minimum, P=%d" % P, flush=True)
+    W = 8
+    rng = np.random.default_rng(P)
+    rows = []
+    for frac, floor in ((0.5, 0.0), (0.9, 0.0), (0.99, 0.0), (0.9, 1e-20), (0.7, -3.5)):
+        x = np.exp(3 * rng.standard_normal(P)).astype(np.float32)
+        x[rng.random(P) < frac] = np.float32(floor)
+        rows.append(x)
+    scores = np.stack(rows)
+    d = torch.from_numpy(scores).cuda()
+    shape = fk.make_shape(P + W)
+    for k in (W, W + 1, P // 50 + W, P // 5, P // 2, P, P + W):   # thresholds above, at and inside the tied mass
+        idx = ctx.fkv_select_topk(shape, d, k).cpu().numpy()
+        for r in range(len(rows)):
+            np.testing.assert_array_equal(idx[r], oracle.select_topk(scores[r], W, k), err_msg="row %d k %d" % (r, k))
+
+
 def test_select_ragged(ctx):
     lengths = [300, 1000, 57, 8, 2049]
     ks = [100, 8, 57, 8, 1024]
