@@ -27,9 +27,9 @@ int select_long_threshold(void) { return kOneBlockMax; }
 int select_long_chunk(void) { return kLongChunk; }
 
 // info words of a row's state
-// Launch R (2..4) writes the interval it derived to words 3(R-2).. and reads what launch R-1 wrote,
+// Launch R (2..4) writes the interval it derived to words 4(R-2).. and reads what launch R-1 wrote,
 // so no launch reads words another block of the same launch writes.
-enum { kInfLo = 0, kInfS = 1, kInfRem = 2, kInfMax = 12, kInfNotMin = 13 };
+enum { kInfLo = 0, kInfS = 1, kInfRem = 2, kInfCount = 3, kInfSlot = 4, kInfMax = 12, kInfNotMin = 13 };
 
 struct LongRow {
   const float *base;  // row pointer rounded down to 16 bytes
@@ -66,13 +66,14 @@ __device__ __forceinline__ LongRow locate_long(const SelectArgs &a) {
 
 // Interval [lo, lo + 2^s) and rank after `rounds` completed rounds, from the state the previous
 // launches left: round 1 starts from the row's key range.
-struct Interval { uint32_t lo, remaining; int s; };
+struct Interval { uint32_t lo, remaining, count; int s; };  // count: keys of the row inside the interval
 __device__ __forceinline__ Interval initial_interval(const LongRow &r) {
   Interval v;
   const uint32_t kmax = r.st[kLongInfo + kInfMax], kmin = ~r.st[kLongInfo + kInfNotMin];
   v.lo = kmin;
   v.s = kmax == kmin ? 0 : 32 - __clz(kmax - kmin);
   v.remaining = (uint32_t)r.kp;
+  v.count = (uint32_t)r.P;
   return v;
 }
 
@@ -124,26 +125,30 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_long_round(SelectArgs a) {
   if (kRound <= 2) {
     v = initial_interval(r);
   } else {
-    const uint32_t *prev = r.st + kLongInfo + 3 * (kRound - 3);
+    const uint32_t *prev = r.st + kLongInfo + kInfSlot * (kRound - 3);
     v.lo = prev[kInfLo];
     v.s = (int)prev[kInfS];
     v.remaining = prev[kInfRem];
+    v.count = prev[kInfCount];
   }
   if (kRound > 1 && v.s > 0) {
     const uint32_t *gh = r.st + (kRound - 2) * kBins;
     for (int i = tid; i < kBins; i += kSelThreads) hist[i] = gh[i];
     __syncthreads();
-    const BinPick p = pick_bin(hist, wsum, bcast, v.remaining);
+    // the histograms leave out the keys equal to the interval's lower end; pick_bin credits them to bin 0
+    const BinPick p = pick_bin(hist, wsum, bcast, v.remaining, v.count);
     const int shift = v.s - min(11, v.s);
     v.lo += p.digit << shift;
     v.s = shift;
     v.remaining = p.remaining;
+    v.count = p.in_bin;
   }
   if (kRound > 1 && r.slice == 0 && tid == 0) {  // read by the next launch
-    uint32_t *mine = r.st + kLongInfo + 3 * (kRound - 2);
+    uint32_t *mine = r.st + kLongInfo + kInfSlot * (kRound - 2);
     mine[kInfLo] = v.lo;
     mine[kInfS] = (uint32_t)v.s;
     mine[kInfRem] = v.remaining;
+    mine[kInfCount] = v.count;
   }
   if (kRound <= 3) {
     if (v.s == 0) return;  // the interval is a single key already
@@ -154,7 +159,8 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_long_round(SelectArgs a) {
 #pragma unroll
     for (int e = 0; e < kLongKpt; ++e) {
       const uint32_t rel = key[e] - v.lo;
-      if (key[e] >= v.lo && rel <= span) atomicAdd(&hist[rel >> shift], 1u);  // key 0 (empty) is below lo
+      if (key[e] > v.lo && rel <= span) atomicAdd(&hist[rel >> shift], 1u);  // key 0 (empty) is below lo; keys == lo
+                                                                             // are recovered from the total
     }
     __syncthreads();
     uint32_t *gh = r.st + (kRound - 1) * kBins;
@@ -203,7 +209,7 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_long_compact(SelectArgs a) 
   }
   __syncthreads();
   uint32_t run_gt = pre[0], run_eq = pre[1];
-  const uint32_t *fin = r.st + kLongInfo + 3 * 2;  // written by the counting launch
+  const uint32_t *fin = r.st + kLongInfo + kInfSlot * 2;  // written by the counting launch
   const uint32_t T = fin[kInfLo], need_eq = fin[kInfRem];
   if (r.slice == 0 && tid == 0) {  // min / max must be zero when the next call's prep launch folds into them
     r.st[kLongInfo + kInfMax] = 0u;
