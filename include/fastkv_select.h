@@ -188,11 +188,19 @@ int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, co
  * sequence b (idx_kv as in fkv_gather_kv) goes to logical token t.  Other slots are not written; a
  * table entry outside [0, n_pages) writes nothing.  v / v_pages may both be NULL.
  *
+ * fkv_compress_kv_paged: KVCompress of a layer in one call, as fkv_compress_kv without the TSP leg
+ * but with the kept rows written into the pages; idx_kv [Hkv][sum budget] receives the kept
+ * positions.
+ *
  * fkv_decode_attention_paged: fkv_decode_attention over the first n_per_seq[b] logical tokens of
  * each sequence.  A table entry outside the pool is clamped into it (wrong result, no fault). */
 int fkv_gather_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const void *v, const int32_t *idx_kv,
                         const int32_t *budget_per_seq, const int32_t *block_table, int32_t max_pages_per_seq,
                         int32_t page_size, int64_t n_pages, void *k_pages, void *v_pages, void *stream);
+int fkv_compress_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, const void *v,
+                          const int32_t *budget_per_seq, const int32_t *block_table, int32_t max_pages_per_seq,
+                          int32_t page_size, int64_t n_pages, void *k_pages, void *v_pages, int32_t *idx_kv,
+                          void *stream);
 int fkv_decode_attention_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k_pages,
                                const void *v_pages, const int32_t *block_table, int32_t max_pages_per_seq,
                                int32_t page_size, int64_t n_pages, const int32_t *n_per_seq, float *out, void *stream);

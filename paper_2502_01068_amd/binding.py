@@ -23,7 +23,7 @@ EXPORTS = [
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
-    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error",
+    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error", "fkv_compress_kv_paged",
 ]
 
 
@@ -80,6 +80,7 @@ def load():
     lib.fkv_gather_kv_per_head.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
     lib.fkv_decode_attention.argtypes = [vp, shp, vp, vp, vp, i32, pi32, vp, vp]
     lib.fkv_gather_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp]
+    lib.fkv_compress_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp, vp]
     lib.fkv_decode_attention_paged.argtypes = [vp, shp, vp, vp, vp, vp, i32, i32, i64, pi32, vp, vp]
     lib.fkv_plan_layer.argtypes = [i32, i32, i32, i32, ctypes.c_double, ctypes.c_double, i32, ctypes.POINTER(FkvLayerPlan)]
     lib.fkv_probe_read.argtypes = [vp, vp, i64, i32, vp]
@@ -322,6 +323,19 @@ class Context:
                                           k_pages.shape[1], k_pages.shape[0], _dev_ptr(k_pages, "k_pages", _BF16),
                                           _dev_ptr(v_pages, "v_pages", _BF16, True), _stream()), "fkv_gather_kv_paged")
         return k_pages, v_pages
+
+    def fkv_compress_kv_paged(self, shape, q_win, k, v, budget_per_seq, block_table, k_pages, v_pages, idx_kv=None):
+        """score -> per-KV-head select -> kept K/V rows into the pages; returns idx_kv [Hkv, sum budget]"""
+        counts, arr = _counts(shape, budget_per_seq)
+        if idx_kv is None:
+            idx_kv = torch.empty((shape.n_kv_heads, sum(counts)), dtype=torch.int32, device=k.device)
+        _check(load().fkv_compress_kv_paged(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
+                                            _dev_ptr(k, "k", _BF16), _dev_ptr(v, "v", _BF16), arr,
+                                            _dev_ptr(block_table, "block_table", (torch.int32,)), block_table.shape[-1],
+                                            k_pages.shape[1], k_pages.shape[0], _dev_ptr(k_pages, "k_pages", _BF16),
+                                            _dev_ptr(v_pages, "v_pages", _BF16), _dev_ptr(idx_kv, "idx_kv", (torch.int32,)),
+                                            _stream()), "fkv_compress_kv_paged")
+        return idx_kv
 
     def fkv_decode_attention_paged(self, shape, q, k_pages, v_pages, block_table, n_per_seq, out=None):
         """q [B,Hq,d] bf16; k_pages, v_pages [n_pages,page_size,Hkv,d]; block_table [B,max_pages] -> out [B,Hq,d] fp32"""

@@ -689,6 +689,39 @@ int fkv_decode_attention_paged(fkv_ctx *ctx, const fkv_shape *shape, const void 
   return decode_common(ctx, shape, q, k_pages, v_pages, FKV_KV_TOKEN_MAJOR, &pg, n_per_seq, out, stream);
 }
 
+namespace {
+// Validation shared by the paged gathers: counts, block table geometry, chunk-id range.
+int check_paged_gather(const Resolved &r, const int32_t *budget_per_seq, const Paging &pg, PagedGatherArgs *g) {
+  int rc = check_counts(r, budget_per_seq, g->cnt_off);
+  if (rc != FKV_OK) return rc;
+  rc = check_paging(pg, r.Hkv);
+  if (rc != FKV_OK) return rc;
+  for (int b = 0; b < r.n_seq; ++b)
+    if (budget_per_seq[b] > (int64_t)pg.max_pages * pg.page_size) return FKV_EINVAL;
+  if ((int64_t)g->cnt_off[r.n_seq] * r.Hkv > (INT32_MAX >> 5)) return FKV_EINVAL;  // 16-byte chunk ids stay below 2^31
+  return FKV_OK;
+}
+int enqueue_gather_paged(fkv_ctx *ctx, const Resolved &r, PagedGatherArgs &g, const void *k, const void *v,
+                         const int32_t *idx_kv, const Paging &pg, void *k_pages, void *v_pages, hipStream_t st) {
+  g.src[0] = static_cast<const uint8_t *>(k);
+  g.src[1] = static_cast<const uint8_t *>(v);
+  g.pages[0] = static_cast<uint8_t *>(k_pages);
+  g.pages[1] = static_cast<uint8_t *>(v_pages);
+  g.idx = idx_kv;
+  g.block_table = pg.table;
+  g.max_pages = pg.max_pages;
+  g.page_shift = page_shift_of(pg.page_size);
+  g.n_pages = (int)pg.n_pages;
+  g.Hkv = r.Hkv;
+  g.total_rows = g.cnt_off[r.n_seq];
+  g.n_seq = r.n_seq;
+  for (int b = 0; b <= r.n_seq; ++b) g.cu[b] = r.cu[b];
+  Timed t(ctx, st, KID_GATHER);
+  const hipError_t e = launch_gather_paged(g, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+}  // namespace
+
 int fkv_gather_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const void *v, const int32_t *idx_kv,
                         const int32_t *budget_per_seq, const int32_t *block_table, int32_t max_pages_per_seq,
                         int32_t page_size, int64_t n_pages, void *k_pages, void *v_pages, void *stream) {
@@ -698,34 +731,47 @@ int fkv_gather_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *k, con
   if (!k || !idx_kv || !k_pages) return FKV_ENULL;
   if ((v == nullptr) != (v_pages == nullptr)) return FKV_ENULL;
   PagedGatherArgs g{};
-  rc = check_counts(r, budget_per_seq, g.cnt_off);
-  if (rc != FKV_OK) return rc;
   const Paging pg{block_table, max_pages_per_seq, page_size, n_pages};
-  rc = check_paging(pg, r.Hkv);
+  rc = check_paged_gather(r, budget_per_seq, pg, &g);
   if (rc != FKV_OK) return rc;
-  for (int b = 0; b < r.n_seq; ++b)
-    if (budget_per_seq[b] > (int64_t)max_pages_per_seq * page_size) return FKV_EINVAL;
-  if ((int64_t)g.cnt_off[r.n_seq] * r.Hkv > (INT32_MAX >> 5)) return FKV_EINVAL;  // 16-byte chunk ids stay below 2^31
   if (misaligned(k) || misaligned(v) || misaligned(k_pages) || misaligned(v_pages)) return FKV_EALIGN;
   rc = check_ctx(ctx, r);
   if (rc != FKV_OK) return rc;
-  g.src[0] = static_cast<const uint8_t *>(k);
-  g.src[1] = static_cast<const uint8_t *>(v);
-  g.pages[0] = static_cast<uint8_t *>(k_pages);
-  g.pages[1] = static_cast<uint8_t *>(v_pages);
-  g.idx = idx_kv;
-  g.block_table = block_table;
-  g.max_pages = max_pages_per_seq;
-  g.page_shift = page_shift_of(page_size);
-  g.n_pages = (int)n_pages;
-  g.Hkv = r.Hkv;
-  g.total_rows = g.cnt_off[r.n_seq];
-  g.n_seq = r.n_seq;
-  for (int b = 0; b <= r.n_seq; ++b) g.cu[b] = r.cu[b];
+  return enqueue_gather_paged(ctx, r, g, k, v, idx_kv, pg, k_pages, v_pages, static_cast<hipStream_t>(stream));
+}
+
+int fkv_compress_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, const void *v,
+                          const int32_t *budget_per_seq, const int32_t *block_table, int32_t max_pages_per_seq,
+                          int32_t page_size, int64_t n_pages, void *k_pages, void *v_pages, int32_t *idx_kv,
+                          void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!q_win || !k || !v || !k_pages || !v_pages || !idx_kv) return FKV_ENULL;
+  PagedGatherArgs g{};
+  const Paging pg{block_table, max_pages_per_seq, page_size, n_pages};
+  rc = check_paged_gather(r, budget_per_seq, pg, &g);
+  if (rc != FKV_OK) return rc;
+  if (misaligned(q_win) || misaligned(k) || misaligned(v) || misaligned(k_pages) || misaligned(v_pages) || misaligned(idx_kv))
+    return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  Timed t(ctx, st, KID_GATHER);
-  const hipError_t e = launch_gather_paged(g, st);
-  return e == hipSuccess ? FKV_OK : hip_fail(e);
+  float *sg = reinterpret_cast<float *>(ctx->ws + ctx->lay.scores_group);
+  rc = enqueue_score(ctx, shape, r, q_win, k, sg, nullptr, nullptr, st);
+  if (rc != FKV_OK) return rc;
+  SelectArgs a{};
+  a.W = r.W;
+  a.n_seq = r.n_seq;
+  for (int b = 0; b <= r.n_seq; ++b) a.cu[b] = r.cu[b];
+  a.n_sets = 0;
+  fill_rowset(&a.set[a.n_sets++], sg, r.sum_p, r.Hkv, idx_kv, g.cnt_off, r.n_seq);
+  {
+    Timed t(ctx, st, KID_SELECT);
+    const hipError_t e = launch_select(a, reinterpret_cast<uint32_t *>(ctx->ws + ctx->lay.sel_long), st);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return enqueue_gather_paged(ctx, r, g, k, v, idx_kv, pg, k_pages, v_pages, st);
 }
 
 int fkv_probe_read(fkv_ctx *ctx, const void *src, int64_t bytes, int32_t streaming, void *stream) {

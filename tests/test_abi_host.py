@@ -136,6 +136,8 @@ def test_entry_points_validate_before_touching_the_context(lib):
     assert lib.fkv_gather_kv_paged(None, ctypes.byref(s), p16, p16, p16, k, p16, 8, 32, 100, p16, p16, None) == fk.FKV_EINVAL  # 8*32 < 512
     assert lib.fkv_gather_kv_paged(None, ctypes.byref(s), p16, p16, p16, k, None, 8, 64, 100, p16, p16, None) == fk.FKV_ENULL  # table
     assert lib.fkv_gather_kv_paged(None, ctypes.byref(s), p16, p16, p16, k, p16, 8, 64, 100, p16, p16, None) == fk.FKV_ENULL   # ctx
+    assert lib.fkv_compress_kv_paged(None, ctypes.byref(s), p16, p16, p16, k, p16, 8, 32, 100, p16, p16, p16, None) == fk.FKV_EINVAL  # 8*32 < 512
+    assert lib.fkv_compress_kv_paged(None, ctypes.byref(s), p16, p16, p16, k, p16, 8, 64, 100, p16, p16, p16, None) == fk.FKV_ENULL   # ctx
     assert lib.fkv_decode_attention_paged(None, ctypes.byref(s), p16, p16, p16, p16, 4, 64, 100, n1, p16, None) == fk.FKV_EINVAL  # 4*64 < 300
     assert lib.fkv_decode_attention_paged(None, ctypes.byref(s), p16, p16, p16, p16, 8, 64, 0, n1, p16, None) == fk.FKV_EINVAL   # no pages
     assert lib.fkv_decode_attention_paged(None, ctypes.byref(s), p16, p16, p16, p16, 8, 64, 100, n1, p16, None) == fk.FKV_ENULL  # ctx

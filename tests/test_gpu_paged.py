@@ -119,6 +119,11 @@ def test_paged_full_size_pipeline(ctx):
         np.testing.assert_array_equal(kp_h[table[0, t // ps], t % ps, g], s["k"][idx_h[g, t], g])
     untouched = np.setdiff1d(np.arange(n_pages), table[0])
     assert not kp_h[untouched].any()
+    # the one-call variant fills a fresh pool identically and returns the same indices
+    kp2, vp2 = torch.zeros_like(kp), torch.zeros_like(vp)
+    idx2 = ctx.fkv_compress_kv_paged(shape, q, k, v, budget, torch.from_numpy(table).cuda(), kp2, vp2)
+    assert torch.equal(idx2, idx)
+    assert torch.equal(kp2.view(torch.int16), kp.view(torch.int16)) and torch.equal(vp2.view(torch.int16), vp.view(torch.int16))
     qd = dev_bf16(wl.normal_bf16(71, 0, "q_win", (1, 32, 128)))
     a = ctx.fkv_decode_attention_paged(shape, qd, kp, vp, torch.from_numpy(table).cuda(), budget)
     b = ctx.fkv_decode_attention(shape, qd, kc, vc, budget, "compact")
