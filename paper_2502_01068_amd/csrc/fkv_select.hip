@@ -11,7 +11,9 @@
 //      spreads the keys over the 2048 LDS bins (fp32 exponents would crowd them into a few
 //      dozen) and makes a constant row cost no pass at all.  After the first pass the few keys
 //      left in the interval are collected into LDS, one per thread, and the remaining passes
-//      run on that list;
+//      run on that list.  Keys equal to the interval's lower end are never histogrammed (a row
+//      may hold thousands of them: probabilities that underflowed to zero); their count is the
+//      difference between the interval's key count and the histogram's total;
 //   2. a scan of the per-item keep counts (in-wave through an LDS table, across waves through
 //      wave totals) gives every kept key its output offset in index order: all keys > T and
 //      the first `need_eq` keys == T by index.
