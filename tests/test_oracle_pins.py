@@ -485,3 +485,10 @@ def test_workload_recipe():
     ref = torch.from_numpy(f).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     np.testing.assert_array_equal(wl.f32_to_bf16_bits(f), ref)
     assert wl.algorithmic_bytes(32768, 6554, 2048) == 193874576
+    # the per-config totals of the byte model: K once, scores and indices written + read once, rows read + written
+    assert round(wl.algorithmic_bytes(2048, 512, 256) / 1e6, 1) == 14.9
+    assert round(wl.algorithmic_bytes(131072, 26214, 13107) / 1e6, 1) == 815.8
+    L, k, b = 32768, 6554, 2048
+    by_hand = (L * 8 * 128 * 2 + 8 * 32 * 128 * 2 + 2 * 4 * 9 * (L - 8) + 2 * 4 * (k + 8 * b)
+               + 2 * k * 4096 * 2 + 2 * 2 * 8 * b * 128 * 2)
+    assert wl.algorithmic_bytes(L, k, b) == by_hand
