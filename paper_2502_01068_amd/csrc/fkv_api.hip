@@ -216,6 +216,7 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
       const int cap_own = n_sub * 32 - halo;
       if (cap_own < 1) continue;
       fits = true;
+      f.n_sub_max = n_sub;
       total = clusters = 0;
       f.cl0[0] = 0;
       for (int b = 0; b < r.n_seq && fits; ++b) {

@@ -89,6 +89,7 @@ struct FusedArgs {
   float2 *cpartial;        // [Hkv*32][cpartial_stride]: per cluster (max, sum)
   int cpartial_stride;
   int n_wg;                // blocks of the launch (all resident at once)
+  int n_sub_max;           // most 32-token sub-tiles any block of the launch computes
   int n_clusters;
   unsigned long long timeout_ticks;  // bound of the grid wait, 100 MHz ticks
   int own[FKV_MAX_SEQS];             // prefix tokens owned by each block of sequence b

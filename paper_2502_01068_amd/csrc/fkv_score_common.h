@@ -97,6 +97,51 @@ __device__ __forceinline__ void stream_head(const ScoreArgs &a, const bf16x8 (&q
   }
 }
 
+// The same stream with the sub-tiles loaded straight from global memory into the wave's LDS tile
+// (gfx950's 128-bit LDS-direct loads: lane l of a load instruction lands at tile offset 16 l), so no
+// registers hold a tile while the previous one is being consumed.  The XOR swizzle moves to the global
+// side: the lane that owns LDS column c' of token slot t fetches the row's column c' ^ (t & 15).
+// Per sub-tile: wait for its loads, run the MFMAs off the tile, start the next sub-tile's loads into
+// the same (now free) tile, run fn while they are in flight.
+template <typename F>
+__device__ __forceinline__ void stream_head_direct(const ScoreArgs &a, const bf16x8 (&qa)[8], int tok_base, int Lb,
+                                                   int g, int first, int n_sub, uint8_t *stage, int lane, F fn) {
+  const int c = lane & 15;        // LDS column of this lane within a token slot
+  const int tq = lane >> 4;       // token within the quad of 4 tokens one load instruction covers
+  const int n = lane & 31, hi = lane >> 5;
+  const uint16_t *kbase = a.k + (size_t)vg_kv_head(a, g) * kHeadDim;
+  const size_t tok_stride = (size_t)a.Hkv * kHeadDim;
+  typedef __attribute__((address_space(1))) const void *gptr_t;
+  typedef __attribute__((address_space(3))) void *lptr_t;
+
+  auto issue = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int slot = i * 4 + tq;
+      int t = first + st * kSub + slot;
+      t = min(max(t, 0), Lb - 1);
+      const uint16_t *src = kbase + (size_t)(tok_base + t) * tok_stride + ((c ^ (slot & 15)) << 3);
+      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(stage + i * 1024), 16, 0, 0);
+    }
+  };
+  issue(0);
+#pragma unroll 1
+  for (int st = 0; st < n_sub; ++st) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tile has landed in LDS
+    wave_lds_sync();
+    floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const u32x4 kb = *reinterpret_cast<const u32x4 *>(stage + n * 256 + (((hi * 8 + s) ^ (n & 15)) << 4));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], __builtin_bit_cast(bf16x8, kb), acc, 0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): every lane's operands have left the tile
+    wave_lds_sync();
+    if (st + 1 < n_sub) issue(st + 1);   // in flight while fn runs
+    fn(st, acc);
+  }
+}
+
 // Folds the per-lane running (max, sum) pairs of a wave's 32 softmax rows over the 32 token
 // lanes, through a wave-private LDS transpose (`scratch` >= 4480 bytes, 4-byte aligned).
 // In: mx[r], sm[r] of row m = (r/4)*8 + (lane/32)*4 + r%4 for token lane%32.

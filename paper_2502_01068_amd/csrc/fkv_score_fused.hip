@@ -2,7 +2,7 @@
 //
 // The softmax normaliser of every window row depends on all keys, so a block cannot turn its
 // logits into probabilities until every block has seen its share of K.  Here the logits wait in
-// registers: each block owns a contiguous token range small enough that its logits (5 MFMA
+// registers: each block owns a contiguous token range small enough that its logits (up to 8 MFMA
 // sub-tiles x 16 accumulator registers per lane) stay on chip, all blocks are resident at once
 // (one per CU), and a grid-wide exchange of the per-row (max, sum) pairs sits between the K
 // stream and the probability / pooling / averaging phase:
@@ -14,18 +14,19 @@
 //            results of its sequence in a fixed order (bit-reproducible)
 //   phase 3  probabilities from the kept logits, window sum, LDS pooling, head means, write
 //
-// Used when the batch fits the resident grid (about 37K tokens on 256 CUs); longer inputs take
+// Used when the batch fits the resident grid (about 64K tokens on 256 CUs); longer inputs take
 // the two-pass kernels.  The wait in phase 2 is bounded: a block that does not see the grid
 // complete within the time limit raises the context's error flag and skips phase 3.
 #include "fkv_score_common.h"
 
 namespace fkv {
 
-constexpr int kFusedSub = 5;                   // sub-tiles (of 32 tokens) a block keeps in registers
-constexpr int kFusedSlots = kFusedSub * kSub;  // 160
+constexpr int kFusedSubShort = 5;  // sub-tiles (of 32 tokens) a block keeps in registers: the variant for inputs
+constexpr int kFusedSubLong = 8;   // that fit 5 per block carries less register-select work per logit
+constexpr int kFusedSlotsMax = kFusedSubLong * kSub;
 constexpr int kClusterSize = 16;
 
-int fused_slots(void) { return kFusedSlots; }
+int fused_slots(void) { return kFusedSlotsMax; }
 int fused_cluster_size(void) { return kClusterSize; }
 
 // Cross-block exchange without cache maintenance.  The L2 caches of the chip's XCDs are not
@@ -57,11 +58,13 @@ __device__ __forceinline__ void block_publish() {
   __syncthreads();
 }
 
+template <int kFusedSub>
 __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs f) {
+  constexpr int kFusedSlots = kFusedSub * kSub;
   __shared__ __attribute__((aligned(16))) uint8_t lds_all[kWaves * kStageBytes];
   __shared__ float cst_lds[kWaves][kRowsPerGroup];
   __shared__ unsigned flag_lds[2];
-  float(*s_head)[kFusedSlots] = reinterpret_cast<float(*)[kFusedSlots]>(lds_all);  // [Hkv*4][160]
+  float(*s_head)[kFusedSlots] = reinterpret_cast<float(*)[kFusedSlots]>(lds_all);  // [Hkv*4][slots]
   float(*g_sum)[kFusedSlots] =
       reinterpret_cast<float(*)[kFusedSlots]>(lds_all + kMaxKvHeads * kMaxGroup * kFusedSlots * 4);
   static_assert((kMaxKvHeads * kMaxGroup + kMaxKvHeads) * kFusedSlots * 4 <= kWaves * kStageBytes, "LDS reuse");
@@ -95,7 +98,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
     float mx[16], sm[16];
 #pragma unroll
     for (int q = 0; q < 16; ++q) { mx[q] = kNegBig; sm[q] = 0.f; }
-    stream_head(a, qa, tok_base, Lb, g, c0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
+    stream_head_direct(a, qa, tok_base, Lb, g, c0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
       const int tok = c0 + st * kSub + n;
       const bool counted = (tok >= o0 && tok < o1) || (last && tok >= P && tok < Lb);
 #pragma unroll
@@ -244,13 +247,16 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
 }
 
 hipError_t launch_score_fused(const ScoreArgs &a, const FusedArgs &f, hipStream_t s) {
-  hipLaunchKernelGGL(k_score_fused, dim3(f.n_wg), dim3(kThreads), 0, s, a, f);
+  if (f.n_sub_max <= kFusedSubShort)
+    hipLaunchKernelGGL(k_score_fused<kFusedSubShort>, dim3(f.n_wg), dim3(kThreads), 0, s, a, f);
+  else
+    hipLaunchKernelGGL(k_score_fused<kFusedSubLong>, dim3(f.n_wg), dim3(kThreads), 0, s, a, f);
   return hipGetLastError();
 }
 
 int score_fused_max_blocks_per_cu(void) {
   int n = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_score_fused, kThreads, 0) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_score_fused<kFusedSubLong>, kThreads, 0) != hipSuccess) return 0;
   return n;
 }
 

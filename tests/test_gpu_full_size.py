@@ -64,6 +64,13 @@ def test_config2_32k_two_pass():
     _full_check(32768, 6554, 2048, "avg", seed=1, score_path=1)
 
 
+@pytest.mark.parametrize("L", [45000, 61440])
+def test_single_pass_kernel_long_variant(L):
+    """Inputs between 37K and 64K tokens: the single-pass kernel keeps up to 8 sub-tiles of logits per block."""
+    print("case: forced single-pass path, L=%d" % L, flush=True)
+    _full_check(L, wl.round_half_up(0.2 * L), 2048, "max", seed=5, score_path=2)
+
+
 def test_config3_128k():
     print("case: config3 L=131072 avg", flush=True)
     _full_check(131072, 26214, 13107, "avg", seed=0)
