@@ -242,7 +242,7 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
                     const int32_t *k_tsp_per_seq, void *x_out, int32_t *idx_tsp, void *stream);
 
 /* Which kernels compute the scores.  0 (default): the single-pass kernel (K read once; all its
- * blocks must be resident at once, about 37K tokens per call on 256 CUs) when the batch fits,
+ * blocks must be resident at once, about 64K tokens per call on 256 CUs) when the batch fits,
  * else the two-pass kernels; 1: always two-pass; 2: single-pass or FKV_EUNSUPPORTED.  Both give
  * the same scores up to fp32 summation order. */
 int fkv_set_score_path(fkv_ctx *ctx, int mode);
