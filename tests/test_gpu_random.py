@@ -153,14 +153,15 @@ def test_random_decode(ctx, case):
         off += n
 
 
-@pytest.mark.parametrize("case", range(10))
+@pytest.mark.parametrize("case", range(12))
 def test_random_medium_batches_scores(ctx, case):
     """Ragged batches of a few thousand to tens of thousands of tokens: many blocks and clusters per
-    sequence on the single-pass path (totals under its limit) and the two-pass path (totals above)."""
+    sequence on both variants of the single-pass kernel (totals under their limits) and on the two-pass
+    path (totals above)."""
     from parity import assert_scores_close
     rng = np.random.default_rng(7000 + case)
     B = int(rng.integers(1, 8))
-    budget = 36000 if case % 2 == 0 else 90000
+    budget = (36000, 90000, 60000)[case % 3]   # 5-sub-tile single pass, two-pass, 8-sub-tile single pass
     cuts = np.sort(rng.integers(0, budget, size=B - 1)) if B > 1 else np.array([], np.int64)
     lengths = [max(8, int(x)) for x in np.diff(np.concatenate([[0], cuts, [budget]]))]
     pool_mode = ("avg", "max")[case % 2]
