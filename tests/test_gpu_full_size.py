@@ -114,12 +114,14 @@ def test_config4_ragged(budget):
     ctx.close()
 
 
-def test_config2_repeatability_under_load():
-    """The single-pass kernel's grid exchange and the select's tie handling must not depend on
-    timing: 1500 back-to-back calls over 3 rotating input sets, two contexts alternating on two
-    streams for the second half, every output compared with the first call's on the device."""
-    print("case: repeatability L=32768, 1500 calls", flush=True)
-    L, k_tsp, budget = 32768, 6554, 2048
+@pytest.mark.parametrize("L,n_calls", [(32768, 1500), (61440, 600)])
+def test_repeatability_under_load(L, n_calls):
+    """The single-pass kernel's grid exchange (both register-capacity variants), its LDS-direct K
+    stream and the select's tie handling must not depend on timing: back-to-back calls over 3 rotating
+    input sets, two contexts alternating on two streams for the second half, every output compared
+    with the first call's on the device."""
+    print("case: repeatability L=%d, %d calls" % (L, n_calls), flush=True)
+    k_tsp, budget = wl.round_half_up(0.2 * L), 2048
     shape = fk.make_shape(L, pool_mode="max")
     gen = torch.Generator(device="cuda")
     sets = []
@@ -143,7 +145,7 @@ def test_config2_repeatability_under_load():
             bad += (o["idx_kv"] != ref["idx_kv"]).sum() + (o["idx_tsp"] != ref["idx_tsp"]).sum()
             bad += (o["x_out"].view(torch.int16) != ref["x_out"].view(torch.int16)).sum()
 
-        for it in range(750):
+        for it in range(n_calls // 2):
             outs[0] = call(ctxs[0], sets[it % 3], outs[0])
             check(outs[0], first[it % 3])
         torch.cuda.synchronize()
@@ -152,7 +154,7 @@ def test_config2_repeatability_under_load():
         bads = [torch.zeros((), dtype=torch.int64, device="cuda") for _ in range(2)]
         for st in streams:
             st.wait_stream(torch.cuda.current_stream())
-        for it in range(375):
+        for it in range(n_calls // 4):
             for i in (0, 1):
                 with torch.cuda.stream(streams[i]):
                     j = (it + i) % 3
