@@ -214,8 +214,8 @@ int fkv_probe_read(fkv_ctx *ctx, const void *src, int64_t bytes, int32_t streami
 
 /* Diagnostics of Sec. 3 on device-resident results.  Both run one block per row on `stream`.
  *
- * fkv_index_overlap: count_out[r] = number of indices A_r and B_r share, for n_rows pairs of ascending, duplicate-free int32
- * index lists (Sec. 3.1: overlap of the critical-token sets of two layers; the overlap ratio is
+ * fkv_index_overlap: count_out[r] = number of indices A_r and B_r share, for n_rows pairs of
+ * ascending, duplicate-free int32 index lists (Sec. 3.1: overlap of the critical-token sets of two layers; the overlap ratio is
  * the count over the set size).  Row r of a starts at a + r*a_stride (elements), likewise b; a
  * stride of 0 compares every row with the same list.  n_a, n_b >= 0.  count_out [n_rows] int32,
  * device.  Unsorted input gives an undefined count (never an out-of-bounds access).
