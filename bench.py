@@ -51,17 +51,27 @@ def run_chain(args):
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     from parity import dev_bf16
 
-    L, budget, n_layers, tsp_layer = 32768, 2048, 32, 15
+    L, n_layers, tsp_layer = int(args.chain_length), 32, 15
+    budget = wl.round_half_up(0.0625 * L)   # 2048 at 32768 tokens
     k_tsp = wl.round_half_up(0.2 * L)
+    seeded = L == 32768
+    gen = torch.Generator(device="cuda")
     torch.cuda.set_device(0)
     ctx = fk.Context(max_total_tokens=L, max_seqs=1, device=0)
     layers = []
     for layer in range(n_layers):
         Lc, keep, kv_budget = fk.fkv_plan_layer(layer, n_layers, tsp_layer, L, 0.2, budget / L)
         assert (keep in (0, k_tsp)) and kv_budget == min(budget, Lc)
-        h = wl.make_sequence(args.seed, Lc, layer=layer, with_x=(layer == tsp_layer))
-        d = {n: dev_bf16(h[n]) for n in ("q_win", "k", "v")}
-        d["x"] = dev_bf16(h["x"]) if layer == tsp_layer else None
+        if seeded:
+            h = wl.make_sequence(args.seed, Lc, layer=layer, with_x=(layer == tsp_layer))
+            d = {n: dev_bf16(h[n]) for n in ("q_win", "k", "v")}
+            d["x"] = dev_bf16(h["x"]) if layer == tsp_layer else None
+        else:  # same shapes and distribution, drawn on the device (host generation takes minutes at 128K)
+            gen.manual_seed(args.seed * 1000 + layer)
+            d = {"q_win": torch.randn((8, 32, 128), device="cuda", generator=gen).bfloat16(),
+                 "k": torch.randn((Lc, 8, 128), device="cuda", generator=gen).bfloat16(),
+                 "v": torch.randn((Lc, 8, 128), device="cuda", generator=gen).bfloat16()}
+            d["x"] = torch.randn((Lc, 4096), device="cuda", generator=gen).bfloat16() if layer == tsp_layer else None
         d["shape"] = fk.make_shape(Lc, pool_mode=args.pool)
         d["L"] = Lc
         d["out"] = None
@@ -121,17 +131,19 @@ def run_chain(args):
     total_bytes = sum(wl.algorithmic_bytes(d["L"], k_tsp if d["x"] is not None else 0, min(budget, d["L"]))
                       for d in layers)
     print(json.dumps({
-        "metric": "end-to-end selection time of the 32-layer chain at L=32768", "value": ms, "unit": "ms",
+        "metric": "end-to-end selection time of the 32-layer chain at L=%d" % L, "value": ms, "unit": "ms",
         "n_gpus": 1, "steps": n, "warmup": max(args.warmup // 4, 2), "ms_per_step": ms, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16 inputs, fp32 accumulate and scores, int32 indices",
-        "data": "synthetic (seeded N(0,1) bf16 + 1% planted heavy keys, independent per layer)",
-        "config": {"workload": "config5_chain: 32 layers, TSP layer 15, L=32768 -> 6554, kv budget 2048, pool %s 7" % args.pool},
+        "data": "synthetic (seeded N(0,1) bf16 + 1% planted heavy keys, independent per layer)" if seeded else
+                "synthetic (N(0,1) bf16 drawn on the device, independent per layer)",
+        "config": {"workload": "config5_chain: 32 layers, TSP layer 15, L=%d -> %d, kv budget %d, pool %s 7" % (
+            L, k_tsp, budget, args.pool)},
         "path": {"launch": "one HIP graph replay per chain", "eager_ms": eager_ms,
                  "two_lanes_ms": two_lane_ms, "token_layers": tokens, "token_layers_per_s": tokens / (ms * 1e-3), "algorithmic_bytes": total_bytes,
                  "achieved_GBps": total_bytes / (ms * 1e-3) / 1e9,
                  "frac_of_peak": total_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "context": {"paper": "the paper's token-importance estimation costs 0.04 s per 32K prefill on one A100 SXM "
-                             "(App. D.4) - another machine and software stack, context only"}}))
+        "context": {"paper": "the paper's token-importance estimation costs 0.04 / 0.08 / 0.15 s per 32K / 64K / 128K "
+                             "prefill on one A100 SXM (App. D.4) - another machine and software stack, context only"}}))
     assert ctx.fkv_query_error() == 0
     ctx.close()
 
@@ -199,6 +211,8 @@ def main():
     ap.add_argument("--workload", default="config2_L32768", choices=sorted(WORKLOADS) + ["config5_chain", "decode"])
     ap.add_argument("--pool", default="avg", choices=["avg", "max"])
     ap.add_argument("--pool-kernel", type=int, default=7, help="odd pooling kernel size (the paper uses 7)")
+    ap.add_argument("--chain-length", type=int, default=32768, help="context length of config5_chain (the paper's "
+                    "overhead table also lists 65536 and 131072); lengths other than 32768 draw inputs on the GPU")
     ap.add_argument("--tsp-rate", type=float, default=None, help="override the workload's TSP keep count with round-half-up(rate * L)")
     ap.add_argument("--kv-rate", type=float, default=None, help="override the workload's KV budget with round-half-up(rate * L)")
     ap.add_argument("--sets", type=int, default=4, help="independent input sets rotated over the steps")
