@@ -148,6 +148,56 @@ def run_chain(args):
     ctx.close()
 
 
+def run_logits_probe(args):
+    """The window-logits contraction alone at config 2's shape (L = 32768, 32 q / 8 kv heads, W = 8), on the
+    matrix cores and as wavefront FMAs, over 4 rotating K tensors; the read-only probe over the same
+    bytes gives the floor both share."""
+    import torch
+    from paper_2502_01068_amd import binding as fk
+    L = 32768
+    torch.cuda.set_device(0)
+    ctx = fk.Context(max_total_tokens=L, max_seqs=1, device=0)
+    shape = fk.make_shape(L)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(args.seed)
+    q = torch.randn((8, 32, 128), device="cuda", generator=gen).bfloat16()
+    ks = [torch.randn((L, 8, 128), device="cuda", generator=gen).bfloat16() for _ in range(4)]
+    keys = torch.empty((256,), dtype=torch.int32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        for i in range(args.warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / args.steps
+
+    mfma_us = timed(lambda i: ctx.fkv_probe_logits(shape, q, ks[i % 4], True, keys))
+    a = fk.Context.decode_row_keys(keys, shape)
+    fma_us = timed(lambda i: ctx.fkv_probe_logits(shape, q, ks[i % 4], False, keys))
+    b = fk.Context.decode_row_keys(keys, shape)
+    read_us = timed(lambda i: ctx.fkv_probe_read(ks[i % 4], False))
+    import numpy as np
+    assert np.allclose(a, b, rtol=1e-5, atol=1e-4), "the two variants disagree"
+    k_bytes = L * 8 * 128 * 2
+    flops = 2.0 * 8 * 32 * 128 * L
+    print(json.dumps({
+        "metric": "window-logits contraction at L=32768: matrix cores vs wavefront FMA", "value": mfma_us, "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": mfma_us * 1e-3, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 inputs, fp32 accumulate", "data": "synthetic N(0,1) bf16",
+        "config": {"workload": "logits_probe: L=32768, 32 q / 8 kv heads, d=128, W=8, 4 rotating K tensors"},
+        "path": {"mfma_us": mfma_us, "fma_us": fma_us, "read_only_us": read_us, "fma_over_mfma": fma_us / mfma_us,
+                 "k_bytes": k_bytes, "mfma_GBps": k_bytes / (mfma_us * 1e-6) / 1e9, "fma_GBps": k_bytes / (fma_us * 1e-6) / 1e9,
+                 "fma_TFLOPs": flops / (fma_us * 1e-6) / 1e12,
+                 "timing": "HIP events around back-to-back launches (each probe call also runs a 1-block clearing kernel)"}}))
+    assert ctx.fkv_query_error() == 0
+    ctx.close()
+
+
 def run_decode(args):
     """Decode-step attention of one new token over the compacted cache (budget 2048 per KV head,
     what config 2 keeps) and, for comparison, over the uncompressed 32768-token cache."""
@@ -208,7 +258,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="config2_L32768", choices=sorted(WORKLOADS) + ["config5_chain", "decode"])
+    ap.add_argument("--workload", default="config2_L32768", choices=sorted(WORKLOADS) + ["config5_chain", "decode", "logits_probe"])
     ap.add_argument("--pool", default="avg", choices=["avg", "max"])
     ap.add_argument("--pool-kernel", type=int, default=7, help="odd pooling kernel size (the paper uses 7)")
     ap.add_argument("--chain-length", type=int, default=32768, help="context length of config5_chain (the paper's "
@@ -230,6 +280,8 @@ def main():
         return run_chain(args)
     if args.workload == "decode":
         return run_decode(args)
+    if args.workload == "logits_probe":
+        return run_logits_probe(args)
 
     import numpy as np
     import torch

@@ -212,6 +212,16 @@ int fkv_decode_attention_paged(fkv_ctx *ctx, const fkv_shape *shape, const void 
  * ("k_probe_read"). */
 int fkv_probe_read(fkv_ctx *ctx, const void *src, int64_t bytes, int32_t streaming, void *stream);
 
+/* Second measurement aid: the window-logits contraction of Eq. 1 alone (q.k for the Hq*W window rows
+ * and every token of one sequence), on the matrix cores as the score kernels run it (use_mfma != 0)
+ * or as wavefront FMAs (use_mfma == 0), for timing the two against each other on the same K stream.
+ * row_keys [Hkv*32] uint32, device: entry g*32 + i*8 + w receives the largest raw logit (no scale, no
+ * mask) of window row w of the i-th head of KV group g as an order-preserving key (larger float <=>
+ * larger key; bit 31 set: key ^ 0x80000000 is the float's bits, else ~key), 0 for rows the shape
+ * does not have.  Single sequence, G <= 4. */
+int fkv_probe_logits(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, int32_t use_mfma,
+                     uint32_t *row_keys, void *stream);
+
 /* Diagnostics of Sec. 3 on device-resident results.  Both run one block per row on `stream`.
  *
  * fkv_index_overlap: count_out[r] = number of indices A_r and B_r share, for n_rows pairs of

@@ -23,7 +23,7 @@ EXPORTS = [
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
-    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error", "fkv_compress_kv_paged",
+    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error", "fkv_compress_kv_paged", "fkv_probe_logits",
 ]
 
 
@@ -83,6 +83,7 @@ def load():
     lib.fkv_compress_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp, vp]
     lib.fkv_decode_attention_paged.argtypes = [vp, shp, vp, vp, vp, vp, i32, i32, i64, pi32, vp, vp]
     lib.fkv_plan_layer.argtypes = [i32, i32, i32, i32, ctypes.c_double, ctypes.c_double, i32, ctypes.POINTER(FkvLayerPlan)]
+    lib.fkv_probe_logits.argtypes = [vp, shp, vp, vp, i32, vp, vp]
     lib.fkv_probe_read.argtypes = [vp, vp, i64, i32, vp]
     lib.fkv_index_overlap.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
     lib.fkv_mass_recall.argtypes = [vp, vp, i64, i32, vp, i64, i32, i32, vp, vp]
@@ -355,6 +356,25 @@ class Context:
         """Read-only launch over the tensor's bytes (size must be a multiple of 64 KiB)."""
         _check(load().fkv_probe_read(self.handle, _dev_ptr(src, "src"), src.numel() * src.element_size(),
                                      1 if streaming else 0, _stream()), "fkv_probe_read")
+
+    def fkv_probe_logits(self, shape, q_win, k, use_mfma=True, row_keys=None):
+        """Largest raw logit of every (head, window row) over all tokens -> fp32 [Hq, W] (G <= 4, one sequence)."""
+        if row_keys is None:
+            row_keys = torch.empty((shape.n_kv_heads * 32,), dtype=torch.int32, device=k.device)
+        _check(load().fkv_probe_logits(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
+                                       _dev_ptr(k, "k", _BF16), 1 if use_mfma else 0,
+                                       _dev_ptr(row_keys, "row_keys", (torch.int32,)), _stream()), "fkv_probe_logits")
+        return row_keys
+
+    @staticmethod
+    def decode_row_keys(row_keys, shape):
+        """Order-preserving keys of fkv_probe_logits -> fp32 [Hq, W]."""
+        import numpy as np
+        key = row_keys.cpu().numpy().view(np.uint32)
+        bits = np.where(key & 0x80000000, key ^ np.uint32(0x80000000), ~key).astype(np.uint32)
+        g_size = shape.n_q_heads // shape.n_kv_heads
+        vals = bits.view(np.float32).reshape(shape.n_kv_heads, 4, 8)[:, :g_size, :shape.window]
+        return vals.reshape(shape.n_q_heads, shape.window)
 
     def fkv_index_overlap(self, a, b, count_out=None):
         """a [R,n_a], b [R,n_b] (or [n_b]: one list for every row) ascending int32 -> shared-index counts [R] int32"""

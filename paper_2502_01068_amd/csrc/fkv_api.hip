@@ -788,6 +788,28 @@ int fkv_probe_read(fkv_ctx *ctx, const void *src, int64_t bytes, int32_t streami
   return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 
+int fkv_probe_logits(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, int32_t use_mfma,
+                     uint32_t *row_keys, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (r.n_seq != 1 || r.vsh != 0) return FKV_EUNSUPPORTED;
+  if (!q_win || !k || !row_keys) return FKV_ENULL;
+  if (misaligned(q_win) || misaligned(k) || misaligned(row_keys)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  ScoreArgs a{};
+  a.q_win = static_cast<const uint16_t *>(q_win);
+  a.k = static_cast<const uint16_t *>(k);
+  a.Hq = r.Hq; a.Hkv = r.Hkv; a.G = r.G; a.W = r.W;
+  a.V = r.V; a.vsh = r.vsh;
+  fill_map(r, &a.map);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timed t(ctx, st, KID_PROBE);
+  const hipError_t e = launch_probe_logits(a, row_keys, ctx->n_cu > 0 ? ctx->n_cu : 256, use_mfma != 0, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+
 int fkv_index_overlap(fkv_ctx *ctx, const int32_t *a, int64_t a_stride, int32_t n_a, const int32_t *b,
                       int64_t b_stride, int32_t n_b, int32_t n_rows, int32_t *count_out, void *stream) {
   if (n_rows < 0 || n_a < 0 || n_b < 0 || a_stride < 0 || b_stride < 0) return FKV_EINVAL;

@@ -186,6 +186,8 @@ hipError_t launch_mass_recall(const DiagRecallArgs &p, int n_rows, hipStream_t s
 
 // ---- read-bandwidth probe -----------------------------------------------------------------
 hipError_t launch_probe_read(const void *src, int64_t bytes, bool streaming, int n_blocks, uint32_t *sink, hipStream_t s);
+struct ScoreArgs;
+hipError_t launch_probe_logits(const ScoreArgs &a, uint32_t *rowkeys, int n_blocks, bool mfma, hipStream_t s);
 
 // ---- gather -----------------------------------------------------------------------------
 struct GatherJob {

@@ -83,3 +83,24 @@ def test_probe_read_runs(ctx):
     assert int(buf.sum()) == 0 and ctx.fkv_query_error() == 0
     with pytest.raises(fk.FkvError):
         ctx.fkv_probe_read(buf[:1000])
+
+
+@pytest.mark.parametrize("L,Hq,Hkv,W", [(2048, 32, 8, 8), (1000, 6, 2, 5), (32768, 32, 8, 8)])
+def test_probe_logits_variants_agree(L, Hq, Hkv, W):
+    """The matrix-core and the wavefront-FMA variants of the logits probe compute the same products:
+    their row maxima agree with each other and with a plain fp32 matrix product."""
+    print("case: logits probe L=%d Hq=%d Hkv=%d W=%d" % (L, Hq, Hkv, W), flush=True)
+    s = wl.make_sequence(90, L, window=W, n_q_heads=Hq, n_kv_heads=Hkv, with_v=False, with_x=False)
+    c = fk.Context(max_total_tokens=L, max_seqs=1)
+    try:
+        shape = fk.make_shape(L, n_q_heads=Hq, n_kv_heads=Hkv, window=W)
+        q, k = dev_bf16(s["q_win"]), dev_bf16(s["k"])
+        a = fk.Context.decode_row_keys(c.fkv_probe_logits(shape, q, k, True), shape)
+        b = fk.Context.decode_row_keys(c.fkv_probe_logits(shape, q, k, False), shape)
+        qf, kf = wl.bf16_bits_to_f32(s["q_win"]), wl.bf16_bits_to_f32(s["k"])
+        G = Hq // Hkv
+        ref = np.stack([[(kf[:, h // G, :] @ qf[w, h, :]).max() for w in range(W)] for h in range(Hq)])
+        np.testing.assert_allclose(a, ref, rtol=1e-5, atol=1e-4)
+        np.testing.assert_allclose(b, ref, rtol=1e-5, atol=1e-4)
+    finally:
+        c.close()
