@@ -104,3 +104,38 @@ def test_probe_logits_variants_agree(L, Hq, Hkv, W):
         np.testing.assert_allclose(b, ref, rtol=1e-5, atol=1e-4)
     finally:
         c.close()
+
+
+def test_profile_facility_counts_launches_and_times(ctx):
+    """The per-kernel timing facility bench.py relies on: every launch of a call is counted under its
+    kernel's name, the times are positive and add up to about the wall time of the calls, reading
+    clears the accumulators, and disabling stops the accounting."""
+    import time
+    print("case: profile facility", flush=True)
+    L = 8192
+    s = wl.make_sequence(91, L)
+    shape = fk.make_shape(L, pool_mode="avg")
+    q, k, v, x = (dev_bf16(s[n]) for n in ("q_win", "k", "v", "x"))
+    out = None
+    for _ in range(3):
+        out = ctx.fkv_compress_kv(shape, q, k, v, 512, x=x, k_tsp_per_seq=1638, out=out)
+    torch.cuda.synchronize()
+    ctx.fkv_profile_enable(True)
+    ctx.fkv_profile_read()
+    n = 20
+    t0 = time.perf_counter()
+    for _ in range(n):
+        out = ctx.fkv_compress_kv(shape, q, k, v, 512, x=x, k_tsp_per_seq=1638, out=out)
+    prof = ctx.fkv_profile_read()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    used = {name: mc for name, mc in prof.items() if mc[1]}
+    assert set(used) == {"k_score_fused", "k_select", "k_gather"}, used
+    assert all(c == n for _, c in used.values())
+    total = sum(ms for ms, _ in used.values())
+    assert all(0.0 < ms / c < 1.0 for ms, c in used.values())
+    assert 0.3 * wall_ms < total < 1.5 * wall_ms, (total, wall_ms)
+    assert all(c == 0 for _, c in ctx.fkv_profile_read().values())      # reading cleared the accumulators
+    ctx.fkv_profile_enable(False)
+    ctx.fkv_compress_kv(shape, q, k, v, 512, x=x, k_tsp_per_seq=1638, out=out)
+    assert all(c == 0 for _, c in ctx.fkv_profile_read().values())
+    assert len(prof) == 9 and "k_probe_read" in prof and "k_decode" in prof
