@@ -63,3 +63,64 @@ def test_compress_kv_graph_replays_match_eager(score_path):
         _eq(eager[1 - which], e2)
     assert ctx.fkv_query_error() == 0
     ctx.close()
+
+
+def test_serving_step_graph_replays_match_eager():
+    """A serving-style step recorded as one graph: KVCompress into a paged cache, decode over the pages,
+    and a long-row select (the multi-launch chain); replays with changed inputs must match eager runs."""
+    print("case: graph capture of paged compress + paged decode + long select", flush=True)
+    L, budget, ps, Hkv = 6000, 512, 16, 8
+    n_pages = budget // ps + 9
+    ctx = fk.Context(max_total_tokens=40008, max_seqs=1)
+    shape = fk.make_shape(L, pool_mode="avg")
+    long_shape = fk.make_shape(40008)
+    rng = np.random.default_rng(3)
+    table = torch.from_numpy(rng.permutation(n_pages)[: budget // ps].astype(np.int32)[None, :]).cuda()
+    seqs = [wl.make_sequence(40 + i, L, n_heavy=30, with_x=False) for i in range(2)]
+    dev = [{n: dev_bf16(s[n]) for n in ("q_win", "k", "v")} for s in seqs]
+    qd = [dev_bf16(wl.normal_bf16(50 + i, 0, "q_win", (1, 32, 128))) for i in range(2)]
+    rows = [torch.from_numpy(wl.random_scores(60 + i, 2, 40000, ties=0.2)).cuda() for i in range(2)]
+    buf = {n: dev[0][n].clone() for n in dev[0]}
+    buf["qd"], buf["rows"] = qd[0].clone(), rows[0].clone()
+    kp = torch.zeros((n_pages, ps, Hkv, 128), dtype=torch.bfloat16, device="cuda")
+    vp = torch.zeros_like(kp)
+    idx = torch.empty((Hkv, budget), dtype=torch.int32, device="cuda")
+    dec = torch.empty((1, 32, 128), dtype=torch.float32, device="cuda")
+    sel = torch.empty((2, 9000), dtype=torch.int32, device="cuda")
+
+    def step(b):
+        ctx.fkv_compress_kv_paged(shape, b["q_win"], b["k"], b["v"], budget, table, kp, vp, idx)
+        ctx.fkv_decode_attention_paged(shape, b["qd"], kp, vp, table, budget, out=dec)
+        ctx.fkv_select_topk(long_shape, b["rows"], 9000, idx_out=sel)
+
+    eager = []
+    for i in range(2):
+        step({**dev[i], "qd": qd[i], "rows": rows[i]})
+        torch.cuda.synchronize()
+        eager.append([t.clone() for t in (kp, vp, idx, dec, sel)])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(buf)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(buf)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        which = rep % 2
+        for n in dev[which]:
+            buf[n].copy_(dev[which][n])
+        buf["qd"].copy_(qd[which])
+        buf["rows"].copy_(rows[which])
+        for t in (kp, vp, idx, dec, sel):
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((kp, vp, idx, dec, sel), eager[which]):
+            a, b = (t.view(torch.int16) if t.dtype == torch.bfloat16 else t for t in (got, want))
+            assert torch.equal(a, b)
+        step({**dev[1 - which], "qd": qd[1 - which], "rows": rows[1 - which]})   # eager work between replays
+        torch.cuda.synchronize()
+    assert ctx.fkv_query_error() == 0
+    ctx.close()
