@@ -3,8 +3,8 @@
 numpy front end of ``fastkv_oracle.c``: plain CPU loops for the window-attention
 saliency score (Sec. 4.2, Eq. 1), per-head pooling, group / all-head means (Eq. 2,
 App. B.1), top-k with the window merged in (Sec. 4.2) and the row gathers of
-HiddenCompress / KVCompress (App. B.1, Algorithm 1), the decoding step over a cache and the
-two diagnostics of Sec. 3 (set overlap, mass recall).  Only tests, the smoke check and
+HiddenCompress / KVCompress (App. B.1, Algorithm 1), the attention output of the window rows,
+the decoding step over a cache and the two diagnostics of Sec. 3 (set overlap, mass recall).  Only tests, the smoke check and
 the benchmark's CPU-baseline leg may import this package; it shares nothing with the
 GPU library.
 
@@ -76,6 +76,28 @@ def window_attention(q_win, k, scale=None, causal=True, precision="f32", threads
                                   int(bool(causal)), _ptr(out))
     if rc != 0:
         raise ValueError("orc_window_attention failed: %d" % rc)
+    return out
+
+
+def window_output(q_win, k, v, scale=None, causal=True, precision="f64", threads=None):
+    """The layer's attention output at the W window positions: out[w, h] = sum over the keys j
+    visible to position L-W+w of Att[h, L-W+w, j] * v[j, g(h)], with the same probabilities Eq. 1
+    sums.  q_win [W,Hq,d], k, v [L,Hkv,d] (uint16 bf16).  Returns [W,Hq,d]."""
+    q_win, k, v = _u16(q_win, 3), _u16(k, 3), _u16(v, 3)
+    W, Hq, d = q_win.shape
+    L, Hkv, d2 = k.shape
+    if d2 != d or v.shape != k.shape:
+        raise ValueError("shape mismatch")
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty((W, Hq, d), dtype=_real(precision))
+    lib = _lib(precision)
+    if threads is not None:
+        lib.orc_set_threads(int(threads))
+    rc = lib.orc_window_output(_ptr(q_win), _ptr(k), _ptr(v), L, Hq, Hkv, d, W, ctypes.c_double(scale),
+                               int(bool(causal)), _ptr(out))
+    if rc != 0:
+        raise ValueError("orc_window_output failed: %d" % rc)
     return out
 
 

@@ -5,7 +5,8 @@
  * FastKV (arXiv 2502.01068): window attention scores (Sec. 4.2, Eq. 1), pooling,
  * head / GQA-group averaging (Eq. 2; App. B.1 "KVCompress"), top-k with the window
  * tokens merged in (Sec. 4.2), and the row gathers of HiddenCompress / KVCompress
- * (App. B.1, Algorithm 1).  It exists to check the GPU library and shares no code
+ * (App. B.1, Algorithm 1), plus the attention output of the window rows and the
+ * decoding step over a cache.  It exists to check the GPU library and shares no code
  * with it.  Nothing in the product path may call it.
  *
  * Every step follows the paper's order: logits -> softmax ("attention score
@@ -104,6 +105,47 @@ int orc_window_attention(const uint16_t *q_win, const uint16_t *k, int L, int Hq
       for (int j = 0; j < P; ++j) row[j] += z[j] / Z;
     }
     free(z);
+  }
+  return err ? -2 : 0;
+}
+
+/* The layer's attention output at the W window positions, from the same probabilities Eq. 1 sums
+ * (Sec. 4.2: Att_l is the layer's own attention matrix; Sec. 5.1 notes the fused attention kernel
+ * does not hand them out, so the estimation step forms them itself):
+ * out[w][h][c] = sum_{j visible to P+w} Att[h, P+w, j] * v[j][g(h)][c].
+ * q_win [W][Hq][d], k, v [L][Hkv][d] bf16 bits; out [W][Hq][d]. */
+int orc_window_output(const uint16_t *q_win, const uint16_t *k, const uint16_t *v, int L, int Hq, int Hkv, int d,
+                      int W, double scale, int causal, real *out) {
+  if (L < W || W < 1 || Hq % Hkv != 0) return -1;
+  const int P = L - W, G = Hq / Hkv;
+  const real sc = (real)scale;
+  int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int h = 0; h < Hq; ++h) {
+    const int g = h / G;
+    real *a = (real *)malloc((size_t)L * sizeof(real));
+    if (!a) { err = 1; continue; }
+    for (int w = 0; w < W; ++w) {
+      const int last = causal ? (P + w) : (L - 1);
+      const uint16_t *qv = q_win + ((size_t)w * Hq + h) * d;
+      real m = 0;
+      for (int j = 0; j <= last; ++j) {
+        const uint16_t *kv = k + ((size_t)j * Hkv + g) * d;
+        real acc = 0;
+        for (int c = 0; c < d; ++c) acc += (real)bf16_to_f32(qv[c]) * (real)bf16_to_f32(kv[c]);
+        a[j] = sc * acc;
+        if (j == 0 || a[j] > m) m = a[j];
+      }
+      real Z = 0;
+      for (int j = 0; j <= last; ++j) { a[j] = REAL_EXP(a[j] - m); Z += a[j]; }
+      real *o = out + ((size_t)w * Hq + h) * d;
+      for (int c = 0; c < d; ++c) {
+        real acc = 0;
+        for (int j = 0; j <= last; ++j) acc += (a[j] / Z) * (real)bf16_to_f32(v[((size_t)j * Hkv + g) * d + c]);
+        o[c] = acc;
+      }
+    }
+    free(a);
   }
   return err ? -2 : 0;
 }

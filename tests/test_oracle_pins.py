@@ -456,6 +456,71 @@ def test_decode_attention_closed_forms():
     np.testing.assert_allclose(out[0], vf[0, 4], atol=1e-6)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_window_output_matches_library_attention(causal):
+    """The last W rows of a full causal attention (library softmax / matrix products, fp64)."""
+    rng = np.random.default_rng(31)
+    L, W, Hq, Hkv, d = 45, 8, 6, 2, 16
+    q_all = _rand_bf16(rng, (L, Hq, d), 1.5)
+    k = _rand_bf16(rng, (L, Hkv, d), 1.5)
+    v = _rand_bf16(rng, (L, Hkv, d))
+    qf, kf, vf = (torch.from_numpy(wl.bf16_bits_to_f32(a)).double() for a in (q_all, k, v))
+    kf, vf = kf.repeat_interleave(3, 1), vf.repeat_interleave(3, 1)
+    for scale in (None, 0.4):
+        sc = 1 / math.sqrt(d) if scale is None else scale
+        z = torch.einsum("ihc,jhc->hij", qf, kf) * sc
+        if causal:
+            z = z.masked_fill(torch.triu(torch.ones(L, L, dtype=torch.bool), 1), -math.inf)
+        ref = torch.einsum("hij,jhc->ihc", torch.softmax(z, dim=-1), vf)[L - W:].numpy()
+        got = oracle.window_output(q_all[L - W:], k, v, scale, causal, "f64")
+        np.testing.assert_allclose(got, ref, rtol=1e-11, atol=1e-13)
+        got32 = oracle.window_output(q_all[L - W:], k, v, scale, causal, "f32")
+        np.testing.assert_allclose(got32, ref, rtol=2e-4, atol=2e-5)
+
+
+def test_window_output_closed_forms_and_structure():
+    rng = np.random.default_rng(32)
+    L, W, Hq, Hkv, d = 29, 8, 4, 2, 8
+    P = L - W
+    q = _rand_bf16(rng, (W, Hq, d))
+    k = _rand_bf16(rng, (L, Hkv, d))
+    v = _rand_bf16(rng, (L, Hkv, d))
+    vf = wl.bf16_bits_to_f32(v).astype(np.float64)
+    # equal keys: row w is the mean of the value rows it can see (P + w + 1 of them when causal)
+    out = oracle.window_output(q, np.zeros_like(k), v, precision="f64")
+    for w in range(W):
+        for h in range(Hq):
+            np.testing.assert_allclose(out[w, h], vf[: P + w + 1, h // 2].mean(0), rtol=1e-13, atol=1e-15)
+    out = oracle.window_output(q, np.zeros_like(k), v, causal=False, precision="f64")
+    np.testing.assert_allclose(out[3, 1], vf[:, 0].mean(0), rtol=1e-13, atol=1e-15)
+    # each window row is the decoding step of its own query over the keys it can see
+    out = oracle.window_output(q, k, v, precision="f64")
+    for w in range(W):
+        n = P + w + 1
+        ref = oracle.decode_attention(q[w], k[:n], v[:n], "token_major", precision="f64")
+        np.testing.assert_allclose(out[w], ref, rtol=1e-12, atol=1e-14)
+    # a key after position P + w must not reach row w: change the last token, rows 0..W-2 keep their bits
+    k2, v2 = k.copy(), v.copy()
+    k2[L - 1], v2[L - 1] = _rand_bf16(rng, (Hkv, d), 3.0), _rand_bf16(rng, (Hkv, d), 3.0)
+    out2 = oracle.window_output(q, k2, v2, precision="f64")
+    np.testing.assert_array_equal(out2[: W - 1], out[: W - 1])
+    assert np.abs(out2[W - 1] - out[W - 1]).max() > 1e-3
+    # the output is linear in V and its weights are the probabilities Eq. 1 sums: with v[j] = e_c * [j == j0]
+    # the window rows add up to the un-pooled window-summed score of token j0
+    j0 = 5
+    onehot = np.zeros((L, Hkv, d), np.float32)
+    onehot[j0, :, 2] = 1.0
+    o = oracle.window_output(q, k, wl.f32_to_bf16_bits(onehot), precision="f64")
+    s = oracle.window_attention(q, k, precision="f64")
+    np.testing.assert_allclose(o[:, :, 2].sum(0), s[:, j0], rtol=1e-12)
+    assert np.abs(o[:, :, :2]).max() == 0.0
+    # constant value rows come back unchanged (the weights of a row add up to one)
+    const = np.broadcast_to(wl.bf16_bits_to_f32(_rand_bf16(rng, (1, Hkv, d))), (L, Hkv, d))
+    o = oracle.window_output(q, k, wl.f32_to_bf16_bits(np.ascontiguousarray(const)), precision="f64")
+    for h in range(Hq):
+        np.testing.assert_allclose(o[:, h], np.broadcast_to(const[0, h // 2], (W, d)), rtol=1e-13)
+
+
 def test_paper_identities():
     g = _gold()
     n_layers, tsp_layer, rate = int(g["n_layers_llama"]), int(g["tsp_layer_llama"]), float(g["tsp_rate"])
