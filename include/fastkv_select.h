@@ -178,6 +178,17 @@ enum { FKV_KV_COMPACT = 0, FKV_KV_TOKEN_MAJOR = 1 };
 int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,
                          int32_t kv_layout, const int32_t *n_per_seq, float *out, void *stream);
 
+/* Attention output of the W window queries of each sequence, formed from the same probabilities
+ * Eq. 1 (Sec. 4.2) sums: out[b][w][h][:] = sum over the keys j visible to position P+w of
+ * Att[h, P+w, j] * v[j][h/G][:] (the layer's fused attention kernel does not expose Att, Sec. 5.1,
+ * so the estimation step forms it; with this call the layer can skip those W rows).
+ * q_win [B][W][Hq][d], k, v [sum L][Hkv][d] bf16 (device); out [B][W][Hq][d] fp32 (device, 16-byte
+ * aligned, written completely).  Uses softmax_scale and causal of `shape` (causal = 0: every window
+ * query sees every key of its sequence); the pooling fields are ignored.  Reads K and V once;
+ * the probabilities enter the value contraction with 16 significant bits. */
+int fkv_window_output(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, const void *v,
+                      float *out, void *stream);
+
 /* Paged cache layout (the serving layout the paper's Limitations section says the method has to
  * fit): a pool of pages [n_pages][page_size][Hkv][d] bf16 per tensor and a DEVICE block table
  * [B][max_pages_per_seq] int32; logical token t of sequence b lives in page

@@ -23,7 +23,7 @@ EXPORTS = [
     "fkv_gather_rows", "fkv_gather_kv", "fkv_compress_kv", "fkv_profile_kernels",
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
-    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error", "fkv_compress_kv_paged", "fkv_probe_logits",
+    "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error", "fkv_compress_kv_paged", "fkv_probe_logits", "fkv_window_output",
 ]
 
 
@@ -79,6 +79,7 @@ def load():
     lib.fkv_score_heads.argtypes = [vp, shp, vp, vp, vp, vp]
     lib.fkv_gather_kv_per_head.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
     lib.fkv_decode_attention.argtypes = [vp, shp, vp, vp, vp, i32, pi32, vp, vp]
+    lib.fkv_window_output.argtypes = [vp, shp, vp, vp, vp, vp, vp]
     lib.fkv_gather_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp]
     lib.fkv_compress_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp, vp]
     lib.fkv_decode_attention_paged.argtypes = [vp, shp, vp, vp, vp, vp, i32, i32, i64, pi32, vp, vp]
@@ -312,6 +313,16 @@ class Context:
         _check(load().fkv_decode_attention(self.handle, ctypes.byref(shape), _dev_ptr(q, "q", _BF16),
                                            _dev_ptr(k, "k", _BF16), _dev_ptr(v, "v", _BF16), lay, arr,
                                            _dev_ptr(out, "out", (torch.float32,)), _stream()), "fkv_decode_attention")
+        return out
+
+    def fkv_window_output(self, shape, q_win, k, v, out=None):
+        """q_win [B,W,Hq,d], k, v [sum L,Hkv,d] bf16 -> attention output of the window rows [B,W,Hq,d] fp32"""
+        if out is None:
+            out = torch.empty((shape.n_seq, shape.window, shape.n_q_heads, shape.head_dim), dtype=torch.float32,
+                              device=k.device)
+        _check(load().fkv_window_output(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
+                                        _dev_ptr(k, "k", _BF16), _dev_ptr(v, "v", _BF16),
+                                        _dev_ptr(out, "out", (torch.float32,)), _stream()), "fkv_window_output")
         return out
 
     def fkv_gather_kv_paged(self, shape, k, v, idx_kv, budget_per_seq, block_table, k_pages, v_pages=None):

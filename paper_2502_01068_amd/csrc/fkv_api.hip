@@ -19,7 +19,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-  size_t partial, rowstat, scores_group, scores_tsp, counters, bpartial, cpartial, sel_long, dec_part, total;
+  size_t partial, rowstat, scores_group, scores_tsp, counters, bpartial, cpartial, sel_long, dec_part, wout_o, wout_ms, total;
   int max_stat_blocks;
 };
 
@@ -37,6 +37,9 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
   w.cpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxClusters * sizeof(float2));
   w.sel_long = off;     off += align_up((size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
   w.dec_part = off;     off += align_up((size_t)max_seqs * kMaxKvHeads * kMaxReal * kDecodeMaxSplits * (kHeadDim + 2) * sizeof(float));
+  const size_t wout_slots = (size_t)kWoutBlocks + (size_t)kMaxVGroups * max_seqs;
+  w.wout_o = off;       off += align_up(wout_slots * kRowsPerGroup * kHeadDim * sizeof(float));
+  w.wout_ms = off;      off += align_up(wout_slots * kRowsPerGroup * sizeof(float2));
   w.total = off;
   return w;
 }
@@ -76,7 +79,7 @@ struct fkv_ctx {
 
 namespace {
 
-const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather", "k_score_fused", "k_decode", "k_diag", "k_probe_read"};
+const char *kKernelNames[KID_COUNT] = {"k_stats", "k_combine", "k_scores", "k_select", "k_gather", "k_score_fused", "k_decode", "k_diag", "k_probe_read", "k_wout"};
 
 int hip_fail(hipError_t e) {
   g_last_hip_error = (int)e;
@@ -677,6 +680,41 @@ int decode_common(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const voi
   return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 }  // namespace
+
+int fkv_window_output(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, const void *v,
+                      float *out, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!q_win || !k || !v || !out) return FKV_ENULL;
+  if (misaligned(q_win) || misaligned(k) || misaligned(v) || misaligned(out)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  ctx->ev_prev = nullptr;
+  WoutArgs a{};
+  a.q_win = static_cast<const uint16_t *>(q_win);
+  a.k = static_cast<const uint16_t *>(k);
+  a.v = static_cast<const uint16_t *>(v);
+  a.part_o = reinterpret_cast<float *>(ctx->ws + ctx->lay.wout_o);
+  a.part_ms = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.wout_ms);
+  a.out = out;
+  int tiles_max = 1;
+  for (int b = 0; b <= r.n_seq; ++b) a.cu[b] = r.cu[b];
+  for (int b = 0; b < r.n_seq; ++b) tiles_max = std::max(tiles_max, (r.cu[b + 1] - r.cu[b] + 31) / 32);
+  a.n_seq = r.n_seq; a.Hq = r.Hq; a.Hkv = r.Hkv; a.G = r.G; a.W = r.W;
+  a.V = r.V; a.vsh = r.vsh;
+  // about one block per CU over all (sequence, group) pairs, and at least one tile per wave of a block
+  int splits = kWoutBlocks / (r.V * r.n_seq);
+  splits = std::min(splits, (tiles_max + wout_tiles_per_block_min() - 1) / wout_tiles_per_block_min());
+  a.n_split = std::max(splits, 1);
+  a.causal = shape->causal;
+  const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->head_dim);
+  a.scale_log2e = scale * 1.4426950408889634f;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timed t(ctx, st, KID_WOUT);
+  const hipError_t e = launch_wout(a, st);
+  return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
 
 int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,
                          int32_t kv_layout, const int32_t *n_per_seq, float *out, void *stream) {

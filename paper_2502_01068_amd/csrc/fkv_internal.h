@@ -44,7 +44,7 @@ extern __device__ unsigned long long fkv_block_ticks[1024 * 4];
 #endif
 
 // Kernel ids for the per-kernel timing facility.
-enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_SCORE_FUSED, KID_DECODE, KID_DIAG, KID_PROBE, KID_COUNT };
+enum KernelId { KID_STATS = 0, KID_COMBINE, KID_SCORES, KID_SELECT, KID_GATHER, KID_SCORE_FUSED, KID_DECODE, KID_DIAG, KID_PROBE, KID_WOUT, KID_COUNT };
 
 // Sequence map passed by value in the kernel arguments: where each sequence's tokens
 // start and which block range of the launch works on it.
@@ -164,6 +164,24 @@ struct DecodeArgs {
 };
 int decode_max_splits(void);
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
+
+// ---- attention output of the window rows ------------------------------------------------
+constexpr int kWoutBlocks = 256;  // blocks a launch aims for (one per CU: 128 KiB of LDS each)
+struct WoutArgs {
+  const uint16_t *q_win;  // [B][W][Hq][d]
+  const uint16_t *k, *v;  // [sum L][Hkv][d]
+  float *part_o;          // [n_seq * V][n_split][32][d]: per block, accumulator relative to its own maximum
+  float2 *part_ms;        // [n_seq * V][n_split][32]: per block (max, sum), log2 units
+  float *out;             // [B][W][Hq][d]
+  int cu[FKV_MAX_SEQS + 1];
+  int n_seq, Hq, Hkv, G, W;
+  int V, vsh;             // virtual groups, as in ScoreArgs
+  int n_split;            // blocks per (sequence, virtual group)
+  int causal;
+  float scale_log2e;
+};
+int wout_tiles_per_block_min(void);
+hipError_t launch_wout(const WoutArgs &a, hipStream_t s);
 
 // ---- diagnostics ------------------------------------------------------------------------
 struct DiagOverlapArgs {

@@ -36,7 +36,8 @@ __device__ __forceinline__ void wave_lds_sync() {
 // MFMA A operand for virtual group g: lane (m = lane%32, hi = lane/32) holds, for step s, the 8
 // values d = hi*64 + s*8 .. +7 of query row m (head vg_head0(g) + m/8, window row m%8).  The
 // contraction index may be permuted freely as long as K uses the same permutation.
-__device__ __forceinline__ void load_q(const ScoreArgs &a, int b, int g, int lane, bf16x8 (&qa)[8]) {
+template <typename A>
+__device__ __forceinline__ void load_q(const A &a, int b, int g, int lane, bf16x8 (&qa)[8]) {
   const int m = lane & 31, hi = lane >> 5;
   const int hl = m >> 3, w = m & 7;
   const bool ok = hl < vg_heads(a, g) && w < a.W;

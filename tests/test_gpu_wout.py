@@ -1,0 +1,111 @@
+"""GPU parity of the window rows' attention output (fkv_window_output) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_01068_amd import binding as fk
+from paper_2502_01068_amd import workloads as wl
+from parity import dev_bf16
+
+pytestmark = pytest.mark.gpu
+# Relative to the largest magnitude of the output row (outputs are signed sums that may cancel).  The
+# kernel keeps 16 bits of every probability and accumulates in fp32: 2^-17 per term, far below this.
+TOL = 1e-4
+
+
+def _close(gpu, ref, what):
+    gpu, ref = np.asarray(gpu, np.float64), np.asarray(ref, np.float64)
+    assert gpu.shape == ref.shape, what
+    assert np.isfinite(gpu).all(), what
+    scale = np.abs(ref).max(axis=-1, keepdims=True)
+    err = np.abs(gpu - ref) / scale
+    assert err.max() <= TOL, "%s: max error %.3g of the row scale" % (what, err.max())
+    return float(err.max())
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = fk.Context(max_total_tokens=40000, max_seqs=8)
+    yield c
+    c.close()
+
+
+def _run(ctx, lens, Hq, Hkv, W=8, scale=0.0, causal=True, seed=70, q_scale=1.0):
+    B, d, tot = len(lens), 128, sum(lens)
+    q = wl.normal_bf16(seed, 0, "q_win", (B, W, Hq, d))
+    if q_scale != 1.0:
+        q = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(q) * q_scale)
+    k = wl.normal_bf16(seed, 0, "k", (tot, Hkv, d))
+    v = wl.normal_bf16(seed, 0, "v", (tot, Hkv, d))
+    shape = fk.make_shape(lens, n_q_heads=Hq, n_kv_heads=Hkv, window=W, softmax_scale=scale, causal=causal)
+    out = ctx.fkv_window_output(shape, dev_bf16(q), dev_bf16(k), dev_bf16(v))
+    torch.cuda.synchronize()
+    assert ctx.fkv_query_error() == 0
+    out = out.cpu().numpy()
+    worst, o = 0.0, 0
+    for b, n in enumerate(lens):
+        ref = oracle.window_output(q[b], k[o:o + n], v[o:o + n], scale or None, causal, "f64")
+        worst = max(worst, _close(out[b], ref, "seq %d" % b))
+        o += n
+    return worst
+
+
+@pytest.mark.parametrize("L", [8, 9, 31, 32, 33, 40, 255, 256, 257, 2048, 5000, 8200])
+def test_window_output_lengths(ctx, L):
+    print("case: window output L=%d" % L, flush=True)
+    print("  worst %.2e" % _run(ctx, [L], 32, 8), flush=True)
+
+
+@pytest.mark.parametrize("Hq,Hkv,W,scale,causal", [
+    (32, 8, 8, 0.0, False), (8, 8, 8, 0.25, True), (12, 4, 8, 0.0, True), (64, 8, 8, 0.0, True),
+    (28, 4, 8, 0.0, True), (32, 8, 4, 0.0, True), (32, 8, 1, 0.0, True), (16, 2, 5, 0.05, False),
+])
+def test_window_output_shapes(ctx, Hq, Hkv, W, scale, causal):
+    print("case: window output Hq=%d Hkv=%d W=%d scale=%g causal=%d" % (Hq, Hkv, W, scale, causal), flush=True)
+    print("  worst %.2e" % _run(ctx, [1333], Hq, Hkv, W, scale, causal), flush=True)
+
+
+def test_window_output_ragged_batch(ctx):
+    print("case: window output ragged batch", flush=True)
+    print("  worst %.2e" % _run(ctx, [300, 8, 2049, 64, 4097, 33], 32, 8), flush=True)
+    print("  worst %.2e" % _run(ctx, [777, 1500], 64, 8, seed=71), flush=True)
+
+
+def test_window_output_peaked_rows(ctx):
+    """Large query norms make every row put almost all of its weight on a few keys: the case where
+    rounding the probabilities to 8 bits would show (the kernel keeps 16)."""
+    print("case: window output peaked rows", flush=True)
+    print("  worst %.2e" % _run(ctx, [3000], 32, 8, q_scale=6.0, seed=72), flush=True)
+    print("  worst %.2e" % _run(ctx, [3000], 32, 8, scale=1.0, seed=73), flush=True)
+
+
+def test_window_output_equal_keys_and_repeatability(ctx):
+    print("case: window output equal keys / repeatability", flush=True)
+    L, Hq, Hkv, d, W = 1000, 32, 8, 128, 8
+    q = wl.normal_bf16(74, 0, "q_win", (1, W, Hq, d))
+    v = wl.normal_bf16(74, 0, "v", (L, Hkv, d))
+    shape = fk.make_shape(L)
+    k0 = torch.zeros((L, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    out = ctx.fkv_window_output(shape, dev_bf16(q), k0, dev_bf16(v)).cpu().numpy()[0]
+    vf = wl.bf16_bits_to_f32(v).astype(np.float64)
+    for w in range(W):
+        mean = vf[: L - W + w + 1].mean(0)   # [Hkv, d]
+        _close(out[w], np.repeat(mean, Hq // Hkv, axis=0), "row %d" % w)
+    k = dev_bf16(wl.normal_bf16(74, 0, "k", (L, Hkv, d)))
+    a = ctx.fkv_window_output(shape, dev_bf16(q), k, dev_bf16(v)).clone()
+    b = ctx.fkv_window_output(shape, dev_bf16(q), k, dev_bf16(v))
+    assert torch.equal(a, b)
+
+
+def test_window_output_rejects_bad_arguments(ctx):
+    shape = fk.make_shape(64)
+    q = torch.zeros((1, 8, 32, 128), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((64, 8, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fk.FkvError) as e:
+        ctx.fkv_window_output(shape, q, k, k, out=torch.zeros((8 * 32 * 128 + 1,), dtype=torch.float32, device="cuda")[1:])
+    assert e.value.status == fk.FKV_EALIGN
+    big = fk.make_shape(50000)
+    with pytest.raises(fk.FkvError) as e:
+        ctx.fkv_window_output(big, q, k, k)
+    assert e.value.status == fk.FKV_EWORKSPACE
