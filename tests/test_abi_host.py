@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, name), name
     assert sorted(fk.EXPORTS) == declared
     assert lib.fkv_version() >= 100
-    assert lib.fkv_profile_kernels() == 9
+    assert lib.fkv_profile_kernels() == 10
     assert lib.fkv_strerror(fk.FKV_EALIGN).decode().startswith("device pointer")
 
 

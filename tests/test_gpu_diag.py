@@ -138,4 +138,4 @@ def test_profile_facility_counts_launches_and_times(ctx):
     ctx.fkv_profile_enable(False)
     ctx.fkv_compress_kv(shape, q, k, v, 512, x=x, k_tsp_per_seq=1638, out=out)
     assert all(c == 0 for _, c in ctx.fkv_profile_read().values())
-    assert len(prof) == 9 and "k_probe_read" in prof and "k_decode" in prof
+    assert len(prof) == 10 and "k_probe_read" in prof and "k_decode" in prof
