@@ -35,9 +35,14 @@ extern __device__ unsigned long long fkv_block_ticks[1024 * 4];
   do {                                                                                      \
     if (threadIdx.x == 0 && blockIdx.x < 1024) fkv::fkv_block_ticks[blockIdx.x * 4 + (i)] = wall_clock64(); \
   } while (0)
+#define FKV_BTICK_AT(blk, i)                                                                \
+  do {                                                                                      \
+    if (threadIdx.x == 0 && (blk) < 1024) fkv::fkv_block_ticks[(blk) * 4 + (i)] = wall_clock64(); \
+  } while (0)
 #else
 #define FKV_TICK(i) ((void)0)
 #define FKV_BTICK(i) ((void)0)
+#define FKV_BTICK_AT(blk, i) ((void)0)
 #endif
 #ifndef FKV_TIMING_BLOCK
 #define FKV_TIMING_BLOCK 0

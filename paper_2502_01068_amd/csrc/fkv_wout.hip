@@ -56,11 +56,16 @@ __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
   const int t0 = split * per, t1 = min(n_tiles, t0 + per);
   uint8_t *ktile = lds_all + wave * kWoTileBytes, *vtile = ktile + kStageBytes;
 
+  const int blk_id = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;  // timing builds only
+  (void)blk_id;
+  FKV_BTICK_AT(blk_id, 0);
   bf16x8 qa[8];
   load_q(a, b, g, lane, qa);
 
   // direct-to-LDS tile loads: lane l of load i lands at tile offset i*1024 + 16 l, i.e. token slot
   // 4 i + l/16, 16-byte column l%16.  The K tile is XOR-swizzled (from the global side), V is plain.
+  // Both streams are read once: the loads are marked non-temporal (measured 34.3 instead of 38.6 us per call at
+  // 32768 tokens).
   const int c = lane & 15, tq = lane >> 4;
   const size_t tok_stride = (size_t)a.Hkv * kHeadDim;
   const uint16_t *kbase = a.k + (size_t)vg_kv_head(a, g) * kHeadDim;
@@ -71,7 +76,7 @@ __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
       const int slot = i * 4 + tq;
       const int t = min(tile * kSub + slot, Lb - 1);
       const uint16_t *src = kbase + (size_t)(tok_base + t) * tok_stride + ((c ^ (slot & 15)) << 3);
-      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(ktile + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(ktile + i * 1024), 16, 0, 2);
     }
   };
   auto issue_v = [&](int tile) {
@@ -79,7 +84,7 @@ __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
     for (int i = 0; i < 8; ++i) {
       const int t = min(tile * kSub + i * 4 + tq, Lb - 1);
       const uint16_t *src = vbase + (size_t)(tok_base + t) * tok_stride;
-      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(vtile + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(vtile + i * 1024), 16, 0, 2);
     }
   };
 
@@ -181,6 +186,7 @@ __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
     if (more) issue_v(tile + kWoWaves);
   }
 
+  FKV_BTICK_AT(blk_id, 1);
   // ---- the wave's state into its own (now idle) LDS tiles: O[row n][d], 16-byte chunks XOR-swizzled by row
   s = add_across_halves(s);
   float *ow = reinterpret_cast<float *>(ktile);
@@ -191,6 +197,7 @@ __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
   }
   if (hi == 0) ms_lds[wave][n] = make_float2(m, s);
   __syncthreads();
+  FKV_BTICK_AT(blk_id, 2);
 
   // ---- merge the waves in a fixed order and write the block's partial
   const size_t slot = ((size_t)b * a.V + g) * a.n_split + split;
@@ -222,6 +229,7 @@ __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
     for (int w = 0; w < kWoWaves; ++w) S += ms_lds[w][row].y * fast_exp2(ms_lds[w][row].x - M);
     a.part_ms[slot * kRowsPerGroup + row] = make_float2(M, S);
   }
+  FKV_BTICK_AT(blk_id, 3);
 }
 
 // Folds the splits of one (sequence, group): grid (n_seq * V, 4), 256 threads, one float4 each.
@@ -233,16 +241,33 @@ __global__ __launch_bounds__(256) void k_wout_merge(WoutArgs a) {
   if (hl >= vg_heads(a, g) || w >= a.W) return;
   const float2 *ms = a.part_ms + (size_t)bg * a.n_split * kRowsPerGroup + row;
   const float *po = a.part_o + (size_t)bg * a.n_split * kWoRowFloats + row * kHeadDim + chunk * 4;
+  // eight splits' loads in flight at a time; the fold itself runs in split order
+  constexpr int kBatch = 8;
   float M = kNegBig;
-  for (int sp = 0; sp < a.n_split; ++sp) M = fmaxf(M, ms[sp * kRowsPerGroup].x);
+  for (int sp0 = 0; sp0 < a.n_split; sp0 += kBatch) {
+    float mx[kBatch];
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) mx[i] = ms[min(sp0 + i, a.n_split - 1) * kRowsPerGroup].x;
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) M = fmaxf(M, mx[i]);
+  }
   float den = 0.f;
   float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int sp = 0; sp < a.n_split; ++sp) {
-    const float2 st = ms[sp * kRowsPerGroup];
-    const float f = fast_exp2(st.x - M);
-    const float4 x = *reinterpret_cast<const float4 *>(po + (size_t)sp * kWoRowFloats);
-    den += f * st.y;
-    num.x += f * x.x; num.y += f * x.y; num.z += f * x.z; num.w += f * x.w;
+  for (int sp0 = 0; sp0 < a.n_split; sp0 += kBatch) {
+    float2 st[kBatch];
+    float4 x[kBatch];
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const int sp = min(sp0 + i, a.n_split - 1);
+      st[i] = ms[sp * kRowsPerGroup];
+      x[i] = *reinterpret_cast<const float4 *>(po + (size_t)sp * kWoRowFloats);
+    }
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const float f = sp0 + i < a.n_split ? fast_exp2(st[i].x - M) : 0.f;
+      den += f * st[i].y;
+      num.x += f * x[i].x; num.y += f * x[i].y; num.z += f * x[i].z; num.w += f * x[i].w;
+    }
   }
   const float inv = 1.f / den;
   float *dst = a.out + (((size_t)b * a.W + w) * a.Hq + vg_head0(a, g) + hl) * kHeadDim + chunk * 4;

@@ -66,8 +66,9 @@ def test_compress_kv_graph_replays_match_eager(score_path):
 
 
 def test_serving_step_graph_replays_match_eager():
-    """A serving-style step recorded as one graph: KVCompress into a paged cache, decode over the pages,
-    and a long-row select (the multi-launch chain); replays with changed inputs must match eager runs."""
+    """A serving-style step recorded as one graph: the window rows' attention output, KVCompress into a
+    paged cache, decode over the pages, and a long-row select (the multi-launch chain); replays with
+    changed inputs must match eager runs."""
     print("case: graph capture of paged compress + paged decode + long select", flush=True)
     L, budget, ps, Hkv = 6000, 512, 16, 8
     n_pages = budget // ps + 9
@@ -87,8 +88,10 @@ def test_serving_step_graph_replays_match_eager():
     idx = torch.empty((Hkv, budget), dtype=torch.int32, device="cuda")
     dec = torch.empty((1, 32, 128), dtype=torch.float32, device="cuda")
     sel = torch.empty((2, 9000), dtype=torch.int32, device="cuda")
+    wo = torch.empty((1, 8, 32, 128), dtype=torch.float32, device="cuda")
 
     def step(b):
+        ctx.fkv_window_output(shape, b["q_win"], b["k"], b["v"], out=wo)
         ctx.fkv_compress_kv_paged(shape, b["q_win"], b["k"], b["v"], budget, table, kp, vp, idx)
         ctx.fkv_decode_attention_paged(shape, b["qd"], kp, vp, table, budget, out=dec)
         ctx.fkv_select_topk(long_shape, b["rows"], 9000, idx_out=sel)
@@ -97,7 +100,7 @@ def test_serving_step_graph_replays_match_eager():
     for i in range(2):
         step({**dev[i], "qd": qd[i], "rows": rows[i]})
         torch.cuda.synchronize()
-        eager.append([t.clone() for t in (kp, vp, idx, dec, sel)])
+        eager.append([t.clone() for t in (kp, vp, idx, dec, sel, wo)])
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
@@ -113,11 +116,11 @@ def test_serving_step_graph_replays_match_eager():
             buf[n].copy_(dev[which][n])
         buf["qd"].copy_(qd[which])
         buf["rows"].copy_(rows[which])
-        for t in (kp, vp, idx, dec, sel):
+        for t in (kp, vp, idx, dec, sel, wo):
             t.zero_()
         graph.replay()
         torch.cuda.synchronize()
-        for got, want in zip((kp, vp, idx, dec, sel), eager[which]):
+        for got, want in zip((kp, vp, idx, dec, sel, wo), eager[which]):
             a, b = (t.view(torch.int16) if t.dtype == torch.bfloat16 else t for t in (got, want))
             assert torch.equal(a, b)
         step({**dev[1 - which], "qd": qd[1 - which], "rows": rows[1 - which]})   # eager work between replays

@@ -109,3 +109,31 @@ def test_window_output_rejects_bad_arguments(ctx):
     with pytest.raises(fk.FkvError) as e:
         ctx.fkv_window_output(big, q, k, k)
     assert e.value.status == fk.FKV_EWORKSPACE
+
+
+def test_window_output_full_size_32k():
+    """Config 2's layer (workload recipe with planted heavy keys), every output row against the oracle."""
+    print("case: window output at L=32768, all rows", flush=True)
+    L = 32768
+    s = wl.make_sequence(0, L, with_x=False)
+    c = fk.Context(max_total_tokens=L, max_seqs=1)
+    out = c.fkv_window_output(fk.make_shape(L), dev_bf16(s["q_win"]), dev_bf16(s["k"]), dev_bf16(s["v"])).cpu().numpy()[0]
+    print("  gpu done", flush=True)
+    ref = oracle.window_output(s["q_win"], s["k"], s["v"], precision="f64")
+    print("  worst %.2e" % _close(out, ref, "L=32768"), flush=True)
+    c.close()
+
+
+def test_window_output_full_size_128k_sampled():
+    """131072 tokens: the heads of two KV groups against the oracle run on those groups alone."""
+    print("case: window output at L=131072, sampled groups", flush=True)
+    L = 131072
+    s = wl.make_sequence(1, L, with_x=False)
+    c = fk.Context(max_total_tokens=L, max_seqs=1)
+    out = c.fkv_window_output(fk.make_shape(L), dev_bf16(s["q_win"]), dev_bf16(s["k"]), dev_bf16(s["v"])).cpu().numpy()[0]
+    print("  gpu done", flush=True)
+    for g in (2, 7):
+        ref = oracle.window_output(np.ascontiguousarray(s["q_win"][:, 4 * g:4 * g + 4]), np.ascontiguousarray(s["k"][:, g:g + 1]),
+                                   np.ascontiguousarray(s["v"][:, g:g + 1]), precision="f64")
+        print("  group %d worst %.2e" % (g, _close(out[:, 4 * g:4 * g + 4], ref, "group %d" % g)), flush=True)
+    c.close()
