@@ -232,43 +232,56 @@ __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
   FKV_BTICK_AT(blk_id, 3);
 }
 
-// Folds the splits of one (sequence, group): grid (n_seq * V, 4), 256 threads, one float4 each.
+// Folds the splits of one (sequence, group).  Four lanes share one float4 of the output and take
+// every fourth split each (eight loads in flight per lane), then meet through two lane exchanges;
+// the order of the sums is fixed.  Grid (n_seq * V, 16), 256 threads.
+constexpr int kWoMergeOutputs = 64;  // float4 outputs per block
 __global__ __launch_bounds__(256) void k_wout_merge(WoutArgs a) {
   const int bg = blockIdx.x, b = bg / a.V, g = bg - b * a.V;
-  const int idx = blockIdx.y * 256 + threadIdx.x;
+  const int j = threadIdx.x & 3;
+  const int idx = blockIdx.y * kWoMergeOutputs + (threadIdx.x >> 2);
   const int row = idx >> 5, chunk = idx & 31;
   const int hl = row >> 3, w = row & 7;
-  if (hl >= vg_heads(a, g) || w >= a.W) return;
+  if (hl >= vg_heads(a, g) || w >= a.W) return;  // the four lanes of an output leave together
   const float2 *ms = a.part_ms + (size_t)bg * a.n_split * kRowsPerGroup + row;
   const float *po = a.part_o + (size_t)bg * a.n_split * kWoRowFloats + row * kHeadDim + chunk * 4;
-  // eight splits' loads in flight at a time; the fold itself runs in split order
   constexpr int kBatch = 8;
+  const int per = (a.n_split + 3) >> 2;  // splits j, j+4, ... of this lane
   float M = kNegBig;
-  for (int sp0 = 0; sp0 < a.n_split; sp0 += kBatch) {
+  for (int i0 = 0; i0 < per; i0 += kBatch) {
     float mx[kBatch];
 #pragma unroll
-    for (int i = 0; i < kBatch; ++i) mx[i] = ms[min(sp0 + i, a.n_split - 1) * kRowsPerGroup].x;
+    for (int i = 0; i < kBatch; ++i) mx[i] = ms[min(4 * (i0 + i) + j, a.n_split - 1) * kRowsPerGroup].x;
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) M = fmaxf(M, mx[i]);
   }
+  M = fmaxf(M, __shfl_xor(M, 1));
+  M = fmaxf(M, __shfl_xor(M, 2));
   float den = 0.f;
   float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int sp0 = 0; sp0 < a.n_split; sp0 += kBatch) {
+  for (int i0 = 0; i0 < per; i0 += kBatch) {
     float2 st[kBatch];
     float4 x[kBatch];
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
-      const int sp = min(sp0 + i, a.n_split - 1);
+      const int sp = min(4 * (i0 + i) + j, a.n_split - 1);
       st[i] = ms[sp * kRowsPerGroup];
       x[i] = *reinterpret_cast<const float4 *>(po + (size_t)sp * kWoRowFloats);
     }
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
-      const float f = sp0 + i < a.n_split ? fast_exp2(st[i].x - M) : 0.f;
+      const float f = 4 * (i0 + i) + j < a.n_split ? fast_exp2(st[i].x - M) : 0.f;
       den += f * st[i].y;
       num.x += f * x[i].x; num.y += f * x[i].y; num.z += f * x[i].z; num.w += f * x[i].w;
     }
   }
+#pragma unroll
+  for (int d = 1; d <= 2; d <<= 1) {
+    den += __shfl_xor(den, d);
+    num.x += __shfl_xor(num.x, d); num.y += __shfl_xor(num.y, d);
+    num.z += __shfl_xor(num.z, d); num.w += __shfl_xor(num.w, d);
+  }
+  if (j != 0) return;
   const float inv = 1.f / den;
   float *dst = a.out + (((size_t)b * a.W + w) * a.Hq + vg_head0(a, g) + hl) * kHeadDim + chunk * 4;
   *reinterpret_cast<float4 *>(dst) = make_float4(num.x * inv, num.y * inv, num.z * inv, num.w * inv);
@@ -278,7 +291,7 @@ hipError_t launch_wout(const WoutArgs &a, hipStream_t s) {
   hipLaunchKernelGGL(k_wout_partial, dim3(a.n_split, a.V, a.n_seq), dim3(kWoThreads), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_wout_merge, dim3(a.n_seq * a.V, kWoRowFloats / 4 / 256), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(k_wout_merge, dim3(a.n_seq * a.V, kWoRowFloats / 4 / kWoMergeOutputs), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
