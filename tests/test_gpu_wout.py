@@ -137,3 +137,16 @@ def test_window_output_full_size_128k_sampled():
                                    np.ascontiguousarray(s["v"][:, g:g + 1]), precision="f64")
         print("  group %d worst %.2e" % (g, _close(out[:, 4 * g:4 * g + 4], ref, "group %d" % g)), flush=True)
     c.close()
+
+
+def test_window_output_many_sequences_and_many_splits():
+    """40 short sequences (one block per sequence and group) and one KV head over 70000 tokens (256 splits)."""
+    print("case: window output, 40 sequences", flush=True)
+    c = fk.Context(max_total_tokens=80000, max_seqs=40)
+    rng = np.random.default_rng(5)
+    lens = [int(n) for n in rng.integers(8, 700, size=40)]
+    print("  worst %.2e" % _run(c, lens, 32, 8, seed=75), flush=True)
+    print("case: window output, one KV head, 70000 tokens", flush=True)
+    print("  worst %.2e" % _run(c, [70000], 4, 1, seed=76), flush=True)
+    print("  worst %.2e" % _run(c, [70001], 2, 2, W=3, seed=77), flush=True)
+    c.close()
