@@ -201,3 +201,57 @@ def test_config5_chain_32_layers():
         assert ctx.fkv_query_error() == 0
     finally:
         ctx.close()
+
+
+def test_million_tokens():
+    """One sequence of 1,000,003 tokens (K and V of 2 GB each: byte offsets beyond 2^31, 123 slices per
+    select row, 1955 score blocks).  One KV group is checked against the oracle run on that group
+    alone, every row against properties that hold at any size, the gathers bit for bit."""
+    print("case: 1,000,003 tokens", flush=True)
+    L, Hq, Hkv, d, g = 1_000_003, 32, 8, 128, 5
+    P, keep = L - W, 100_000
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    q = torch.randn((W, Hq, d), device="cuda", generator=gen).bfloat16()
+    k = torch.randn((L, Hkv, d), device="cuda", generator=gen).bfloat16()
+    v = torch.randn((L, Hkv, d), device="cuda", generator=gen).bfloat16()
+    ctx = fk.Context(max_total_tokens=L, max_seqs=1)
+    shape = fk.make_shape(L, pool_mode="max")
+    sg, st = ctx.fkv_score_window(shape, q, k)
+    idx = ctx.fkv_select_topk(shape, sg, keep)
+    k_out, v_out = ctx.fkv_gather_kv(shape, k, v, idx, keep)
+    wo = ctx.fkv_window_output(shape, q, k, v)
+    torch.cuda.synchronize()
+    assert ctx.fkv_query_error() == 0
+    print("  gpu done", flush=True)
+    # properties of every row: count, order, window kept, no dropped score above a kept one
+    assert idx.shape == (Hkv, keep)
+    assert bool((idx[:, 1:] > idx[:, :-1]).all()) and int(idx.min()) >= 0
+    assert torch.equal(idx[:, keep - W:], torch.arange(P, L, device="cuda", dtype=torch.int32).expand(Hkv, W))
+    for h in range(Hkv):
+        kept = torch.zeros(P, dtype=torch.bool, device="cuda")
+        kept[idx[h, : keep - W].long()] = True
+        assert int(kept.sum()) == keep - W
+        assert float(sg[h][kept].min()) >= float(sg[h][~kept].max())
+    # gathers, bit for bit
+    for h in range(Hkv):
+        assert torch.equal(k_out[h].view(torch.int16), k[:, h].index_select(0, idx[h].long()).view(torch.int16))
+        assert torch.equal(v_out[h].view(torch.int16), v[:, h].index_select(0, idx[h].long()).view(torch.int16))
+    # TSP scores are the mean of the group scores
+    assert_scores_close(st.cpu().numpy(), sg.double().mean(0).cpu().numpy(), "tsp = mean of groups")
+    # one group against the oracle
+    t0 = time.time()
+    q_g, k_g, v_g = host_bits(q[:, 4 * g:4 * g + 4]), host_bits(k[:, g:g + 1]), host_bits(v[:, g:g + 1])
+    ref = oracle.score_window(q_g, k_g, 7, "max", precision="f64")  # fp64: a million-term sum in fp32 would blur the reference
+    print("  oracle scores of one group in %.1fs" % (time.time() - t0), flush=True)
+    ref_row = ref["scores_group"][0].astype(np.float32)
+    e = assert_scores_close(sg[g].cpu().numpy(), ref_row, "group %d" % g)
+    flips = assert_index_set(idx[g].cpu().numpy(), oracle.select_topk(ref_row, W, keep), ref_row, W, "group %d" % g)
+    t0 = time.time()
+    ref_o = oracle.window_output(q_g, k_g, v_g, precision="f64")
+    print("  oracle window output of one group in %.1fs" % (time.time() - t0), flush=True)
+    got = wo[0, :, 4 * g:4 * g + 4].double().cpu().numpy()
+    err = float((np.abs(got - ref_o) / np.abs(ref_o).max(axis=-1, keepdims=True)).max())
+    assert err <= 1e-4, err
+    print("  score error %.2e, %d index flips in the tolerance band, window output error %.2e" % (e, flips, err), flush=True)
+    ctx.close()
