@@ -386,6 +386,20 @@ def main():
         step(i)
     wall_ms, dev_ms = timed(args.steps, 0)               # headline: rotating (cold) inputs
 
+    # spread of single steps: one event pair per step (each interval also holds one event record)
+    n_spread = min(args.steps, 200)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_spread + 1)]
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(n_spread):
+        step(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n_spread)])
+    spread = {"p10": float(np.percentile(per_step, 10)), "p50": float(np.percentile(per_step, 50)),
+              "p90": float(np.percentile(per_step, 90)),
+              "note": "device us between events recorded after every step; each interval includes one event record"}
+
     # warm variant: the same buffers every step
     saved = sets
     sets = saved[:1]
@@ -505,7 +519,7 @@ def main():
                      "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_us": per_kernel_us[dominant]},
         "path": {"algorithmic_bytes": total_bytes, "achieved_GBps": total_bytes / (wall_ms * 1e-3) / 1e9,
                  "frac_of_peak": total_bytes / (wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                 "device_ms_per_step": dev_ms, "warm_ms_per_step": warm_wall_ms, "warm_device_ms": warm_dev_ms,
+                 "device_ms_per_step": dev_ms, "warm_ms_per_step": warm_wall_ms, "warm_device_ms": warm_dev_ms, "step_us_spread": spread,
                  "per_kernel_us": per_kernel_us, "event_record_cost_us": event_cost_us,
                  "measured_copy_GBps": copy_gbs, "measured_read_GBps": read_gbs,
                  "frac_of_measured_copy": total_bytes / (wall_ms * 1e-3) / 1e9 / copy_gbs,
