@@ -142,6 +142,10 @@ def test_entry_points_validate_before_touching_the_context(lib):
     assert lib.fkv_decode_attention_paged(None, ctypes.byref(s), p16, p16, p16, p16, 8, 64, 0, n1, p16, None) == fk.FKV_EINVAL   # no pages
     assert lib.fkv_decode_attention_paged(None, ctypes.byref(s), p16, p16, p16, p16, 8, 64, 100, n1, p16, None) == fk.FKV_ENULL  # ctx
     assert lib.fkv_probe_logits(None, ctypes.byref(s), p16, p16, 1, p16, None) == fk.FKV_ENULL   # ctx
+    assert lib.fkv_window_output(None, ctypes.byref(_shape(lengths=7)), p16, p16, p16, p16, None) == fk.FKV_EINVAL  # L < W
+    assert lib.fkv_window_output(None, ctypes.byref(s), p16, p16, None, p16, None) == fk.FKV_ENULL    # v
+    assert lib.fkv_window_output(None, ctypes.byref(s), p16, p16, p16, p8, None) == fk.FKV_EALIGN     # out
+    assert lib.fkv_window_output(None, ctypes.byref(s), p16, p16, p16, p16, None) == fk.FKV_ENULL     # ctx
     assert lib.fkv_probe_read(None, p16, 1000, 0, None) == fk.FKV_EINVAL and lib.fkv_probe_read(None, p16, 65536, 0, None) == fk.FKV_ENULL
     assert lib.fkv_set_wait_limit(None, 5) == fk.FKV_ENULL and lib.fkv_clear_error(None) == fk.FKV_ENULL
     assert lib.fkv_destroy(None) == fk.FKV_ENULL
