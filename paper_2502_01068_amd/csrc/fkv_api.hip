@@ -212,25 +212,40 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
     FusedArgs f{};
     // Fewest 32-token sub-tiles per block for which the batch still fits the resident grid: short
     // inputs then spread over more blocks and each block streams less before the grid exchange.
-    const int halo = a.pool_r + (a.pool_r > r.W ? a.pool_r : r.W);
+    // A block computes its owned tokens plus the pooling halo on both sides; the last block of a
+    // sequence also computes the W window columns, so it can own fewer tokens than the others.
+    const int halo_mid = 2 * a.pool_r;
+    const int halo_last = a.pool_r + (a.pool_r > r.W ? a.pool_r : r.W);
     int total = 0, clusters = 0;
     bool fits = false;
+    // Measured over 2048 .. 32768 tokens: the exchange gets slower with the number of blocks, so a
+    // launch of more than 224 blocks (128 when a block holds a single sub-tile) loses to one more
+    // sub-tile per block.  The first round looks for a layout within those counts, the second
+    // takes whatever fits the resident grid.
+    for (int round = 0; round < 2 && !fits; ++round)
     for (int n_sub = 1; n_sub * 32 <= fused_slots() && !fits && ctx->score_path != 1 && r.V <= kMaxKvHeads; ++n_sub) {
-      const int cap_own = n_sub * 32 - halo;
-      if (cap_own < 1) continue;
+      const int own_mid = n_sub * 32 - halo_mid, own_last = n_sub * 32 - halo_last;
+      if (own_last < 1) continue;
+      const int max_blocks = round == 1 ? ctx->n_cu : std::min(ctx->n_cu, n_sub == 1 ? 128 : 224);
       fits = true;
       f.n_sub_max = n_sub;
       total = clusters = 0;
       f.cl0[0] = 0;
       for (int b = 0; b < r.n_seq && fits; ++b) {
         const int P = r.cu[b + 1] - r.cu[b] - r.W;
-        const int nb_b = (P + cap_own - 1) / cap_own;
+        // largest share per block (fewest blocks) whose remainder fits the last block
+        int own = 0, nb_b = 0;
+        for (int o = own_mid; o >= 1 && P > 0; --o) {
+          const int nb = (P + o - 1) / o;
+          if (P - (nb - 1) * o <= own_last) { own = o; nb_b = nb; break; }
+        }
+        if (P > 0 && nb_b == 0) { fits = false; break; }
         a.map.blk[b] = total;
-        f.own[b] = nb_b ? (P + nb_b - 1) / nb_b : 0;
+        f.own[b] = own;
         total += nb_b;
         clusters += (nb_b + fused_cluster_size() - 1) / fused_cluster_size();
         f.cl0[b + 1] = clusters;
-        if (total > ctx->n_cu || total > kMaxFusedBlocks || clusters > kMaxClusters) fits = false;
+        if (total > max_blocks || total > kMaxFusedBlocks || clusters > kMaxClusters) fits = false;
       }
     }
     if (ctx->score_path == 2 && !(fits && total > 0)) return FKV_EUNSUPPORTED;
