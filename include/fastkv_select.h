@@ -23,10 +23,17 @@
  *   - Two calls that share a context must be ordered on one stream (they share the
  *     context's workspace).  Calls on different contexts may run concurrently on different
  *     streams; while several contexts exist on a device, their single-pass score launches are
- *     chained on the GPU through an event (that event wait cannot be captured into a graph).
+ *     chained on the GPU through an event (that event wait cannot be captured into a graph, and
+ *     graphs that hold single-pass launches of different contexts must not be replayed
+ *     concurrently; force the two-pass kernels with fkv_set_score_path for such use).
  *   - The calling thread's current HIP device must be the context's device and `stream` must
- *     belong to it; the library does not switch devices.
+ *     belong to it; the compute calls do not switch devices (fkv_create makes `device` current for
+ *     its own set-up and puts the caller's device back before it returns).
  *   - bf16 tensors are raw 16-bit patterns.  Scores are fp32, indices int32.
+ *   - Score precision: fp32 accumulation of exact bf16 products; a score agrees with exact
+ *     arithmetic to a few ulp, except that each of the W probabilities it sums is formed with the
+ *     hardware exp2 and is taken as 0 when it lies below fp32's normal range (2^-126): a score may
+ *     fall short by up to W * 2^-126 in absolute terms, and scores that small come out as 0.
  *
  * Tensor layouts (B = n_seq sequences packed along tokens, T_b = cu_seqlens[b], sum L = T_B)
  *   q_win        [B][W][Hq][d]      bf16   queries of the last W positions of each sequence
@@ -101,8 +108,8 @@ int fkv_check_counts(const fkv_shape *shape, const int32_t *count_per_seq);
 size_t fkv_workspace_bytes(int64_t max_total_tokens, int32_t max_seqs);
 
 /* Create a context on HIP device `device`; allocates the workspace once (the only
- * allocation the library ever makes).  fkv_destroy frees it; the caller must have
- * synchronised the streams that used it. */
+ * allocation the library ever makes) and synchronises that device.  fkv_destroy frees it; the
+ * caller must have synchronised the streams that used it. */
 int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_seqs);
 int fkv_destroy(fkv_ctx *ctx);
 
@@ -121,8 +128,9 @@ int fkv_select_topk(fkv_ctx *ctx, const fkv_shape *shape, const float *scores, i
 
 /* gather_rows(X, idx): out[o_b + t][:] = x[T_b + idx[o_b + t]][:] for t < k_b, where
  * o_b = sum_{b'<b} k_b' (HiddenCompress, App. B.1).  Rows are copied bit for bit.
- * Indices must lie in [0, L_b); the kernels clamp an index outside that range into it (a wrong
- * row is copied, nothing is read out of bounds).  The same holds for every gather below. */
+ * Indices must lie in [0, L_b); the kernels clamp an index beyond the sequence into it (a wrong
+ * row is copied, nothing is read out of bounds) and copy nothing for a negative index (the mark
+ * fkv_compress_kv leaves when its score pass failed).  The same holds for every gather below. */
 int fkv_gather_rows(fkv_ctx *ctx, const fkv_shape *shape, const void *x, size_t row_bytes,
                     const int32_t *idx, const int32_t *k_per_seq, void *out, void *stream);
 
@@ -268,16 +276,20 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
  * the same scores up to fp32 summation order. */
 int fkv_set_score_path(fkv_ctx *ctx, int mode);
 
-/* Synchronises the device and reports the context's sticky error flag: 0, or 1 if a block of the
- * single-pass score kernel gave up waiting for the rest of its grid (2 s bound; scores of that
- * call are then unwritten).  Cannot happen while the library's launches are the only work
- * competing for the device's compute units for that long. */
+/* Synchronises the device (hipDeviceSynchronize) and reports the context's sticky error flag: 0, or
+ * 1 if a wave of the single-pass score kernel gave up waiting for the rest of its grid (2 s bound).
+ * Cannot happen while the library's launches are the only work competing for the device's compute
+ * units for that long.  The failure is visible on the device without this call: the blocks that
+ * gave up write NaN scores, and while the flag is set every single-pass score launch of the context
+ * writes only NaN scores, fkv_compress_kv / fkv_compress_kv_paged write -1 into every index and the
+ * gathers copy nothing for those.  The flag stays set until fkv_clear_error. */
 int fkv_query_error(fkv_ctx *ctx, int32_t *flag_out);
 
-/* fkv_set_wait_limit: bound of that wait in microseconds (0 restores the 2 s default, at most 60 s).
- * A block that gives up still leaves the kernel normally and the grid's counters re-arm themselves,
- * so the next call works; a tiny limit is how the failure path is exercised.  fkv_clear_error
- * synchronises the device and resets the flag. */
+/* fkv_set_wait_limit: bound of every wait of the single-pass kernel's grid exchange in microseconds
+ * (0 restores the 2 s default, at most 60 s).  A wave that gives up still leaves the kernel
+ * normally; a tiny limit is how the failure path is exercised.  fkv_clear_error synchronises the
+ * device, empties the exchange's mailboxes (a failed exchange may leave values in them) and resets
+ * the flag; the next call works again. */
 int fkv_set_wait_limit(fkv_ctx *ctx, int64_t microseconds);
 int fkv_clear_error(fkv_ctx *ctx);
 

@@ -150,18 +150,38 @@ def _check(status, where):
         raise FkvError(status, where)
 
 
-def _dev_ptr(t, name, dtypes=None, allow_none=False):
+def _dev_ptr(t, name, dtypes=None, allow_none=False, numel=None, nbytes=None, device=None):
+    """Device pointer of a tensor after the checks the C ABI cannot make (it sees no sizes): the
+    tensor is on the GPU (`device`: on that one), contiguous, of an accepted dtype and holds at
+    least `numel` elements / `nbytes` bytes."""
     if t is None:
         if allow_none:
             return None
         raise ValueError("%s is required" % name)
-    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+    if not getattr(t, "is_cuda", False):
         raise ValueError("%s must be a GPU tensor" % name)
+    if device is not None and t.device.index != device:
+        raise ValueError("%s is on cuda:%s, the context is on cuda:%d" % (name, t.device.index, device))
     if not t.is_contiguous():
         raise ValueError("%s must be contiguous" % name)
     if dtypes is not None and t.dtype not in dtypes:
         raise ValueError("%s has dtype %s, expected one of %s" % (name, t.dtype, dtypes))
+    if numel is not None and t.numel() < numel:
+        raise ValueError("%s holds %d elements, the shape needs %d" % (name, t.numel(), numel))
+    if nbytes is not None and t.numel() * t.element_size() < nbytes:
+        raise ValueError("%s holds %d bytes, the shape needs %d" % (name, t.numel() * t.element_size(), nbytes))
     return ctypes.c_void_p(t.data_ptr())
+
+
+class _Sizes:
+    """Element counts of every tensor of a call, from the host descriptor."""
+
+    def __init__(self, shape):
+        self.total = sum(shape._lengths)
+        self.sum_p = self.total - shape.n_seq * shape.window
+        self.q_win = shape.n_seq * shape.window * shape.n_q_heads * shape.head_dim
+        self.kv = self.total * shape.n_kv_heads * shape.head_dim
+        self.q_dec = shape.n_seq * shape.n_q_heads * shape.head_dim
 
 
 _BF16 = (torch.bfloat16, torch.int16, torch.uint16)
@@ -206,64 +226,74 @@ class Context:
             pass
 
     # ---- the C ABI, same names -----------------------------------------------------------
+    # Every wrapper checks tensor sizes against the host descriptor and the tensors' device against
+    # the context's before the call: the C ABI takes bare pointers and cannot.
+    def _p(self, t, name, dtypes=None, allow_none=False, numel=None, nbytes=None):
+        return _dev_ptr(t, name, dtypes, allow_none, numel, nbytes, self.device)
+
     def fkv_score_window(self, shape, q_win, k, scores_group=None, scores_tsp=None, want_tsp=True):
         """-> (scores_group [Hkv, sum P] fp32, scores_tsp [sum P] fp32 or None)"""
-        total = sum(shape._lengths)
-        sum_p = total - shape.n_seq * shape.window
+        n = _Sizes(shape)
         dev = k.device
         if scores_group is None:
-            scores_group = torch.empty((shape.n_kv_heads, sum_p), dtype=torch.float32, device=dev)
+            scores_group = torch.empty((shape.n_kv_heads, n.sum_p), dtype=torch.float32, device=dev)
         if scores_tsp is None and want_tsp:
-            scores_tsp = torch.empty((sum_p,), dtype=torch.float32, device=dev)
-        _check(load().fkv_score_window(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
-                                       _dev_ptr(k, "k", _BF16), _dev_ptr(scores_group, "scores_group", (torch.float32,)),
-                                       _dev_ptr(scores_tsp, "scores_tsp", (torch.float32,), True), _stream()),
+            scores_tsp = torch.empty((n.sum_p,), dtype=torch.float32, device=dev)
+        _check(load().fkv_score_window(self.handle, ctypes.byref(shape), self._p(q_win, "q_win", _BF16, numel=n.q_win),
+                                       self._p(k, "k", _BF16, numel=n.kv),
+                                       self._p(scores_group, "scores_group", (torch.float32,), numel=shape.n_kv_heads * n.sum_p),
+                                       self._p(scores_tsp, "scores_tsp", (torch.float32,), True, numel=n.sum_p), _stream()),
                "fkv_score_window")
         return scores_group, scores_tsp
 
     def fkv_select_topk(self, shape, scores, k_per_seq, idx_out=None):
         """scores [n_rows, sum P] (or [sum P]) -> idx [n_rows, sum k] int32"""
         counts, arr = _counts(shape, k_per_seq)
+        n = _Sizes(shape)
         n_rows = 1 if scores.dim() == 1 else scores.shape[0]
+        if scores.shape[-1] != n.sum_p:
+            raise ValueError("scores rows hold %d entries, the shape has %d prefix tokens" % (scores.shape[-1], n.sum_p))
         if idx_out is None:
             idx_out = torch.empty((n_rows, sum(counts)), dtype=torch.int32, device=scores.device)
-        _check(load().fkv_select_topk(self.handle, ctypes.byref(shape), _dev_ptr(scores, "scores", (torch.float32,)),
-                                      n_rows, arr, _dev_ptr(idx_out, "idx_out", (torch.int32,)), _stream()),
-               "fkv_select_topk")
+        _check(load().fkv_select_topk(self.handle, ctypes.byref(shape), self._p(scores, "scores", (torch.float32,)),
+                                      n_rows, arr, self._p(idx_out, "idx_out", (torch.int32,), numel=n_rows * sum(counts)),
+                                      _stream()), "fkv_select_topk")
         return idx_out
 
     def fkv_gather_rows(self, shape, x, idx, k_per_seq, out=None):
         """x [sum L, ...] -> out [sum k, ...] (rows copied bit for bit)"""
         counts, arr = _counts(shape, k_per_seq)
+        n = _Sizes(shape)
         row_bytes = x.stride(0) * x.element_size()
+        if x.shape[0] != n.total:
+            raise ValueError("x has %d rows, the shape has %d tokens" % (x.shape[0], n.total))
         if out is None:
             out = torch.empty((sum(counts),) + tuple(x.shape[1:]), dtype=x.dtype, device=x.device)
-        _check(load().fkv_gather_rows(self.handle, ctypes.byref(shape), _dev_ptr(x, "x"), row_bytes,
-                                      _dev_ptr(idx, "idx", (torch.int32,)), arr, _dev_ptr(out, "out"), _stream()),
+        _check(load().fkv_gather_rows(self.handle, ctypes.byref(shape), self._p(x, "x"), row_bytes,
+                                      self._p(idx, "idx", (torch.int32,), numel=sum(counts)), arr,
+                                      self._p(out, "out", nbytes=sum(counts) * row_bytes), _stream()),
                "fkv_gather_rows")
         return out
 
     def fkv_gather_kv(self, shape, k, v, idx_kv, budget_per_seq, k_out=None, v_out=None):
         counts, arr = _counts(shape, budget_per_seq)
+        n = _Sizes(shape)
         tot = sum(counts)
+        n_out = shape.n_kv_heads * tot * shape.head_dim
         if k_out is None:
             k_out = torch.empty((shape.n_kv_heads, tot, shape.head_dim), dtype=k.dtype, device=k.device)
         if v is not None and v_out is None:
             v_out = torch.empty((shape.n_kv_heads, tot, shape.head_dim), dtype=v.dtype, device=v.device)
-        _check(load().fkv_gather_kv(self.handle, ctypes.byref(shape), _dev_ptr(k, "k", _BF16),
-                                    _dev_ptr(v, "v", _BF16, True), _dev_ptr(idx_kv, "idx_kv", (torch.int32,)), arr,
-                                    _dev_ptr(k_out, "k_out"), _dev_ptr(v_out, "v_out", None, True), _stream()),
-               "fkv_gather_kv")
+        _check(load().fkv_gather_kv(self.handle, ctypes.byref(shape), self._p(k, "k", _BF16, numel=n.kv),
+                                    self._p(v, "v", _BF16, True, numel=n.kv),
+                                    self._p(idx_kv, "idx_kv", (torch.int32,), numel=shape.n_kv_heads * tot), arr,
+                                    self._p(k_out, "k_out", _BF16, numel=n_out), self._p(v_out, "v_out", _BF16, True, numel=n_out),
+                                    _stream()), "fkv_gather_kv")
         return k_out, v_out
 
-    def fkv_compress_kv(self, shape, q_win, k, v, budget_per_seq, x=None, k_tsp_per_seq=None, out=None):
-        """One layer of Algorithm 1.  Returns dict(k_out, v_out, idx_kv[, x_out, idx_tsp]).
-        Pass `out` (a dict from a previous call) to reuse the output buffers."""
-        b_counts, b_arr = _counts(shape, budget_per_seq)
-        tsp = x is not None
-        if tsp:
-            t_counts, t_arr = _counts(shape, k_tsp_per_seq)
+    def _compress_outputs(self, shape, k, v, x, b_counts, t_counts, out):
         dev = k.device
+        tsp = x is not None
         if out is None:
             out = {"k_out": torch.empty((shape.n_kv_heads, sum(b_counts), shape.head_dim), dtype=k.dtype, device=dev),
                    "v_out": torch.empty((shape.n_kv_heads, sum(b_counts), shape.head_dim), dtype=v.dtype, device=dev),
@@ -271,110 +301,154 @@ class Context:
             if tsp:
                 out["x_out"] = torch.empty((sum(t_counts),) + tuple(x.shape[1:]), dtype=x.dtype, device=dev)
                 out["idx_tsp"] = torch.empty((sum(t_counts),), dtype=torch.int32, device=dev)
+        return out
+
+    def fkv_compress_kv(self, shape, q_win, k, v, budget_per_seq, x=None, k_tsp_per_seq=None, out=None):
+        """One layer of Algorithm 1.  Returns dict(k_out, v_out, idx_kv[, x_out, idx_tsp]).
+        Pass `out` (a dict from a previous call of the same shape and counts) to reuse the output buffers."""
+        b_counts, b_arr = _counts(shape, budget_per_seq)
+        n = _Sizes(shape)
+        tsp = x is not None
+        t_counts, t_arr = _counts(shape, k_tsp_per_seq) if tsp else ([], None)
+        if tsp and x.shape[0] != n.total:
+            raise ValueError("x has %d rows, the shape has %d tokens" % (x.shape[0], n.total))
+        out = self._compress_outputs(shape, k, v, x, b_counts, t_counts, out)
         row_bytes = x.stride(0) * x.element_size() if tsp else 0
+        n_kv_out = shape.n_kv_heads * sum(b_counts) * shape.head_dim
         _check(load().fkv_compress_kv(
-            self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16), _dev_ptr(k, "k", _BF16),
-            _dev_ptr(v, "v", _BF16), b_arr, _dev_ptr(out["k_out"], "k_out"), _dev_ptr(out["v_out"], "v_out"),
-            _dev_ptr(out["idx_kv"], "idx_kv", (torch.int32,)), _dev_ptr(x, "x", None, True), row_bytes,
-            t_arr if tsp else None, _dev_ptr(out.get("x_out"), "x_out", None, True),
-            _dev_ptr(out.get("idx_tsp"), "idx_tsp", (torch.int32,), True), _stream()), "fkv_compress_kv")
+            self.handle, ctypes.byref(shape), self._p(q_win, "q_win", _BF16, numel=n.q_win),
+            self._p(k, "k", _BF16, numel=n.kv), self._p(v, "v", _BF16, numel=n.kv), b_arr,
+            self._p(out["k_out"], "k_out", _BF16, numel=n_kv_out), self._p(out["v_out"], "v_out", _BF16, numel=n_kv_out),
+            self._p(out["idx_kv"], "idx_kv", (torch.int32,), numel=shape.n_kv_heads * sum(b_counts)),
+            self._p(x, "x", None, True), row_bytes, t_arr,
+            self._p(out.get("x_out"), "x_out", None, not tsp, nbytes=sum(t_counts) * row_bytes),
+            self._p(out.get("idx_tsp"), "idx_tsp", (torch.int32,), not tsp, numel=sum(t_counts)), _stream()),
+            "fkv_compress_kv")
         return out
 
     def fkv_score_heads(self, shape, q_win, k, scores_head=None):
         """-> scores_head [Hq, sum P] fp32: pooled per-head scores (Eq. 1), no head averaging"""
-        sum_p = sum(shape._lengths) - shape.n_seq * shape.window
+        n = _Sizes(shape)
         if scores_head is None:
-            scores_head = torch.empty((shape.n_q_heads, sum_p), dtype=torch.float32, device=k.device)
-        _check(load().fkv_score_heads(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
-                                      _dev_ptr(k, "k", _BF16), _dev_ptr(scores_head, "scores_head", (torch.float32,)),
+            scores_head = torch.empty((shape.n_q_heads, n.sum_p), dtype=torch.float32, device=k.device)
+        _check(load().fkv_score_heads(self.handle, ctypes.byref(shape), self._p(q_win, "q_win", _BF16, numel=n.q_win),
+                                      self._p(k, "k", _BF16, numel=n.kv),
+                                      self._p(scores_head, "scores_head", (torch.float32,), numel=shape.n_q_heads * n.sum_p),
                                       _stream()), "fkv_score_heads")
         return scores_head
 
     def fkv_gather_kv_per_head(self, shape, k, v, idx_head, budget_per_seq, k_out=None, v_out=None):
         counts, arr = _counts(shape, budget_per_seq)
+        n = _Sizes(shape)
         tot = sum(counts)
+        n_out = shape.n_q_heads * tot * shape.head_dim
         if k_out is None:
             k_out = torch.empty((shape.n_q_heads, tot, shape.head_dim), dtype=k.dtype, device=k.device)
         if v is not None and v_out is None:
             v_out = torch.empty((shape.n_q_heads, tot, shape.head_dim), dtype=v.dtype, device=v.device)
-        _check(load().fkv_gather_kv_per_head(self.handle, ctypes.byref(shape), _dev_ptr(k, "k", _BF16),
-                                             _dev_ptr(v, "v", _BF16, True), _dev_ptr(idx_head, "idx_head", (torch.int32,)),
-                                             arr, _dev_ptr(k_out, "k_out"), _dev_ptr(v_out, "v_out", None, True),
+        _check(load().fkv_gather_kv_per_head(self.handle, ctypes.byref(shape), self._p(k, "k", _BF16, numel=n.kv),
+                                             self._p(v, "v", _BF16, True, numel=n.kv),
+                                             self._p(idx_head, "idx_head", (torch.int32,), numel=shape.n_q_heads * tot),
+                                             arr, self._p(k_out, "k_out", _BF16, numel=n_out),
+                                             self._p(v_out, "v_out", _BF16, True, numel=n_out),
                                              _stream()), "fkv_gather_kv_per_head")
         return k_out, v_out
 
     def fkv_decode_attention(self, shape, q, k, v, n_per_seq, layout="compact", out=None):
         """q [B,Hq,d] bf16; k, v [Hkv,sum n,d] ("compact") or [sum n,Hkv,d] ("token_major") -> out [B,Hq,d] fp32"""
-        counts, arr = [int(c) for c in ([n_per_seq] * shape.n_seq if isinstance(n_per_seq, int) else n_per_seq)], None
+        counts = [int(c) for c in ([n_per_seq] * shape.n_seq if isinstance(n_per_seq, int) else n_per_seq)]
+        if len(counts) != shape.n_seq:
+            raise ValueError("need one token count per sequence")
         arr = _i32_array(counts)
+        n = _Sizes(shape)
+        n_cache = sum(counts) * shape.n_kv_heads * shape.head_dim
         if out is None:
             out = torch.empty((shape.n_seq, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device=q.device)
         lay = {"compact": 0, "token_major": 1}[layout]
-        _check(load().fkv_decode_attention(self.handle, ctypes.byref(shape), _dev_ptr(q, "q", _BF16),
-                                           _dev_ptr(k, "k", _BF16), _dev_ptr(v, "v", _BF16), lay, arr,
-                                           _dev_ptr(out, "out", (torch.float32,)), _stream()), "fkv_decode_attention")
+        _check(load().fkv_decode_attention(self.handle, ctypes.byref(shape), self._p(q, "q", _BF16, numel=n.q_dec),
+                                           self._p(k, "k", _BF16, numel=n_cache), self._p(v, "v", _BF16, numel=n_cache), lay, arr,
+                                           self._p(out, "out", (torch.float32,), numel=n.q_dec), _stream()), "fkv_decode_attention")
         return out
 
     def fkv_window_output(self, shape, q_win, k, v, out=None):
         """q_win [B,W,Hq,d], k, v [sum L,Hkv,d] bf16 -> attention output of the window rows [B,W,Hq,d] fp32"""
+        n = _Sizes(shape)
         if out is None:
             out = torch.empty((shape.n_seq, shape.window, shape.n_q_heads, shape.head_dim), dtype=torch.float32,
                               device=k.device)
-        _check(load().fkv_window_output(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
-                                        _dev_ptr(k, "k", _BF16), _dev_ptr(v, "v", _BF16),
-                                        _dev_ptr(out, "out", (torch.float32,)), _stream()), "fkv_window_output")
+        _check(load().fkv_window_output(self.handle, ctypes.byref(shape), self._p(q_win, "q_win", _BF16, numel=n.q_win),
+                                        self._p(k, "k", _BF16, numel=n.kv), self._p(v, "v", _BF16, numel=n.kv),
+                                        self._p(out, "out", (torch.float32,), numel=n.q_win), _stream()), "fkv_window_output")
         return out
+
+    def _paging(self, shape, block_table, k_pages, v_pages, v_required):
+        if block_table.dim() != 2 or block_table.shape[0] != shape.n_seq:
+            raise ValueError("block_table must be [n_seq, max_pages], got %s" % (tuple(block_table.shape),))
+        if k_pages.dim() != 4 or tuple(k_pages.shape[2:]) != (shape.n_kv_heads, shape.head_dim):
+            raise ValueError("k_pages must be [n_pages, page_size, Hkv, d], got %s" % (tuple(k_pages.shape),))
+        if v_pages is not None and tuple(v_pages.shape) != tuple(k_pages.shape):
+            raise ValueError("v_pages must have the shape of k_pages")
+        return (self._p(block_table, "block_table", (torch.int32,)), int(block_table.shape[1]), int(k_pages.shape[1]),
+                int(k_pages.shape[0]), self._p(k_pages, "k_pages", _BF16), self._p(v_pages, "v_pages", _BF16, not v_required))
 
     def fkv_gather_kv_paged(self, shape, k, v, idx_kv, budget_per_seq, block_table, k_pages, v_pages=None):
         """k, v [sum L,Hkv,d]; idx_kv [Hkv,sum budget]; block_table [B,max_pages] int32 (GPU);
         k_pages, v_pages [n_pages,page_size,Hkv,d] are updated in place"""
         counts, arr = _counts(shape, budget_per_seq)
-        _check(load().fkv_gather_kv_paged(self.handle, ctypes.byref(shape), _dev_ptr(k, "k", _BF16),
-                                          _dev_ptr(v, "v", _BF16, True), _dev_ptr(idx_kv, "idx_kv", (torch.int32,)), arr,
-                                          _dev_ptr(block_table, "block_table", (torch.int32,)), block_table.shape[-1],
-                                          k_pages.shape[1], k_pages.shape[0], _dev_ptr(k_pages, "k_pages", _BF16),
-                                          _dev_ptr(v_pages, "v_pages", _BF16, True), _stream()), "fkv_gather_kv_paged")
+        n = _Sizes(shape)
+        if (v is None) != (v_pages is None):
+            raise ValueError("v and v_pages go together")
+        bt, max_pages, page_size, n_pages, kp, vp = self._paging(shape, block_table, k_pages, v_pages, False)
+        _check(load().fkv_gather_kv_paged(self.handle, ctypes.byref(shape), self._p(k, "k", _BF16, numel=n.kv),
+                                          self._p(v, "v", _BF16, True, numel=n.kv),
+                                          self._p(idx_kv, "idx_kv", (torch.int32,), numel=shape.n_kv_heads * sum(counts)), arr,
+                                          bt, max_pages, page_size, n_pages, kp, vp, _stream()), "fkv_gather_kv_paged")
         return k_pages, v_pages
 
     def fkv_compress_kv_paged(self, shape, q_win, k, v, budget_per_seq, block_table, k_pages, v_pages, idx_kv=None):
         """score -> per-KV-head select -> kept K/V rows into the pages; returns idx_kv [Hkv, sum budget]"""
         counts, arr = _counts(shape, budget_per_seq)
+        n = _Sizes(shape)
         if idx_kv is None:
             idx_kv = torch.empty((shape.n_kv_heads, sum(counts)), dtype=torch.int32, device=k.device)
-        _check(load().fkv_compress_kv_paged(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
-                                            _dev_ptr(k, "k", _BF16), _dev_ptr(v, "v", _BF16), arr,
-                                            _dev_ptr(block_table, "block_table", (torch.int32,)), block_table.shape[-1],
-                                            k_pages.shape[1], k_pages.shape[0], _dev_ptr(k_pages, "k_pages", _BF16),
-                                            _dev_ptr(v_pages, "v_pages", _BF16), _dev_ptr(idx_kv, "idx_kv", (torch.int32,)),
+        bt, max_pages, page_size, n_pages, kp, vp = self._paging(shape, block_table, k_pages, v_pages, True)
+        _check(load().fkv_compress_kv_paged(self.handle, ctypes.byref(shape), self._p(q_win, "q_win", _BF16, numel=n.q_win),
+                                            self._p(k, "k", _BF16, numel=n.kv), self._p(v, "v", _BF16, numel=n.kv), arr,
+                                            bt, max_pages, page_size, n_pages, kp, vp,
+                                            self._p(idx_kv, "idx_kv", (torch.int32,), numel=shape.n_kv_heads * sum(counts)),
                                             _stream()), "fkv_compress_kv_paged")
         return idx_kv
 
     def fkv_decode_attention_paged(self, shape, q, k_pages, v_pages, block_table, n_per_seq, out=None):
         """q [B,Hq,d] bf16; k_pages, v_pages [n_pages,page_size,Hkv,d]; block_table [B,max_pages] -> out [B,Hq,d] fp32"""
         counts = [int(c) for c in ([n_per_seq] * shape.n_seq if isinstance(n_per_seq, int) else n_per_seq)]
+        if len(counts) != shape.n_seq:
+            raise ValueError("need one token count per sequence")
         arr = _i32_array(counts)
+        n = _Sizes(shape)
         if out is None:
             out = torch.empty((shape.n_seq, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device=q.device)
-        _check(load().fkv_decode_attention_paged(self.handle, ctypes.byref(shape), _dev_ptr(q, "q", _BF16),
-                                                 _dev_ptr(k_pages, "k_pages", _BF16), _dev_ptr(v_pages, "v_pages", _BF16),
-                                                 _dev_ptr(block_table, "block_table", (torch.int32,)), block_table.shape[-1],
-                                                 k_pages.shape[1], k_pages.shape[0], arr,
-                                                 _dev_ptr(out, "out", (torch.float32,)), _stream()),
+        bt, max_pages, page_size, n_pages, kp, vp = self._paging(shape, block_table, k_pages, v_pages, True)
+        _check(load().fkv_decode_attention_paged(self.handle, ctypes.byref(shape), self._p(q, "q", _BF16, numel=n.q_dec),
+                                                 kp, vp, bt, max_pages, page_size, n_pages, arr,
+                                                 self._p(out, "out", (torch.float32,), numel=n.q_dec), _stream()),
                "fkv_decode_attention_paged")
         return out
 
     def fkv_probe_read(self, src, streaming=False):
         """Read-only launch over the tensor's bytes (size must be a multiple of 64 KiB)."""
-        _check(load().fkv_probe_read(self.handle, _dev_ptr(src, "src"), src.numel() * src.element_size(),
+        _check(load().fkv_probe_read(self.handle, self._p(src, "src"), src.numel() * src.element_size(),
                                      1 if streaming else 0, _stream()), "fkv_probe_read")
 
     def fkv_probe_logits(self, shape, q_win, k, use_mfma=True, row_keys=None):
         """Largest raw logit of every (head, window row) over all tokens -> fp32 [Hq, W] (G <= 4, one sequence)."""
         if row_keys is None:
             row_keys = torch.empty((shape.n_kv_heads * 32,), dtype=torch.int32, device=k.device)
-        _check(load().fkv_probe_logits(self.handle, ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16),
-                                       _dev_ptr(k, "k", _BF16), 1 if use_mfma else 0,
-                                       _dev_ptr(row_keys, "row_keys", (torch.int32,)), _stream()), "fkv_probe_logits")
+        n = _Sizes(shape)
+        _check(load().fkv_probe_logits(self.handle, ctypes.byref(shape), self._p(q_win, "q_win", _BF16, numel=n.q_win),
+                                       self._p(k, "k", _BF16, numel=n.kv), 1 if use_mfma else 0,
+                                       self._p(row_keys, "row_keys", (torch.int32,), numel=shape.n_kv_heads * 32), _stream()),
+               "fkv_probe_logits")
         return row_keys
 
     @staticmethod
@@ -399,9 +473,9 @@ class Context:
             raise ValueError("index rows must be contiguous")
         if count_out is None:
             count_out = torch.empty((rows,), dtype=torch.int32, device=a.device)
-        _check(load().fkv_index_overlap(self.handle, _dev_ptr(a2, "a", (torch.int32,), True), a2.stride(0) if rows > 1 else 0,
-                                        a2.shape[1], _dev_ptr(b, "b", (torch.int32,), True), b_stride, n_b, rows,
-                                        _dev_ptr(count_out, "count_out", (torch.int32,)), _stream()), "fkv_index_overlap")
+        _check(load().fkv_index_overlap(self.handle, self._p(a2, "a", (torch.int32,), True), a2.stride(0) if rows > 1 else 0,
+                                        a2.shape[1], self._p(b, "b", (torch.int32,), True), b_stride, n_b, rows,
+                                        self._p(count_out, "count_out", (torch.int32,), numel=rows), _stream()), "fkv_index_overlap")
         return count_out
 
     def fkv_mass_recall(self, scores, idx, recall_out=None):
@@ -415,10 +489,10 @@ class Context:
             raise ValueError("rows must be contiguous")
         if recall_out is None:
             recall_out = torch.empty((rows,), dtype=torch.float32, device=scores.device)
-        _check(load().fkv_mass_recall(self.handle, _dev_ptr(s2, "scores", (torch.float32,), True),
+        _check(load().fkv_mass_recall(self.handle, self._p(s2, "scores", (torch.float32,), True),
                                       s2.stride(0) if rows > 1 else 0, s2.shape[1],
-                                      _dev_ptr(i2, "idx", (torch.int32,), True), i2.stride(0) if rows > 1 else 0,
-                                      i2.shape[1], rows, _dev_ptr(recall_out, "recall_out", (torch.float32,)),
+                                      self._p(i2, "idx", (torch.int32,), True), i2.stride(0) if rows > 1 else 0,
+                                      i2.shape[1], rows, self._p(recall_out, "recall_out", (torch.float32,), numel=rows),
                                       _stream()), "fkv_mass_recall")
         return recall_out
 

@@ -19,7 +19,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-  size_t partial, rowstat, scores_group, scores_tsp, counters, bpartial, cpartial, sel_long, dec_part, wout_o, wout_ms, total;
+  size_t partial, rowstat, scores_group, scores_tsp, counters, fused_part, fused_lse, sel_long, dec_part, wout_o, wout_ms, total;
   int max_stat_blocks;
 };
 
@@ -33,8 +33,8 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
   w.scores_group = off; off += align_up((size_t)max_tokens * kMaxKvHeads * sizeof(float));
   w.scores_tsp = off;   off += align_up((size_t)max_tokens * sizeof(float));
   w.counters = off;     off += align_up((size_t)kNumCounters * sizeof(unsigned));
-  w.bpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxFusedBlocks * sizeof(float2));
-  w.cpartial = off;     off += align_up((size_t)kMaxKvHeads * kRowsPerGroup * kMaxClusters * sizeof(float2));
+  w.fused_part = off;   off += align_up(kFusedPartBytes);
+  w.fused_lse = off;    off += align_up(kFusedLseBytes);
   w.sel_long = off;     off += align_up((size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
   w.dec_part = off;     off += align_up((size_t)max_seqs * kMaxKvHeads * kMaxReal * kDecodeMaxSplits * (kHeadDim + 2) * sizeof(float));
   const size_t wout_slots = (size_t)kWoutBlocks + (size_t)kMaxVGroups * max_seqs;
@@ -45,9 +45,12 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
 }
 
 // The single-pass score kernel needs its whole grid resident at once (one block per CU).  Two such
-// launches from different streams could each get part of the CUs and wait for the rest forever, so
-// when more than one context lives on a device their single-pass launches are chained on the GPU
-// through an event (no host wait): each waits for the previous one to finish.
+// launches from different streams could each get part of the CUs and wait for the rest until their
+// time limit, so when more than one context lives on a device their single-pass launches are chained
+// on the GPU through an event (no host wait): each waits for the previous one to finish.  Creating
+// the second context of a device synchronises the device once, so that every launch made while
+// only one context existed (those are not followed by an event record) has finished before the
+// first chained launch is enqueued.
 struct FusedGate {
   std::mutex mu;
   int n_ctx = 0;
@@ -55,6 +58,22 @@ struct FusedGate {
   bool recorded = false;
 };
 FusedGate g_gate[16];
+
+// Scratch memory and launch parameters the score kernels need besides the caller's tensors: a
+// view of a context's workspace, or of the library's static scratch array.
+struct ScoreWs {
+  float2 *partial;      // two-pass kernels: per stats block (max, sum) of every softmax row
+  int partial_stride;   // stats blocks `partial` has room for
+  float *rowstat;       // [n_seq][V*32] log-sum-exp per softmax row
+  float2 *fused_part;   // single-pass kernel's mailboxes, nullptr: that kernel is not available
+  float *fused_lse;
+  unsigned *err;
+  int n_cu;             // resident blocks the single-pass kernel may use; also the block-count target of the two-pass launches
+  int score_path;       // 0 auto, 1 two-pass, 2 single-pass or fail
+  unsigned long long wait_ticks;
+  int device;
+  fkv_ctx *prof;        // context whose timing facility brackets the launches, may be nullptr
+};
 
 struct EventPair { hipEvent_t a, b, start; int kid; };  // start = own `a` or the previous launch's `b`
 
@@ -162,7 +181,7 @@ struct Timed {
   hipStream_t s;
   EventPair *ev;
   Timed(fkv_ctx *c, hipStream_t st, int kid) : ctx(c), s(st), ev(nullptr) {
-    if (c->prof_on && c->ev_used < c->ev_pool.size()) {
+    if (c && c->prof_on && c->ev_used < c->ev_pool.size()) {
       ev = &c->ev_pool[c->ev_used++];
       ev->kid = kid;
       if (c->ev_prev) {
@@ -186,14 +205,30 @@ void fill_map(const Resolved &r, SeqMap *m) {
   for (int b = 0; b <= r.n_seq; ++b) m->cu[b] = r.cu[b];
 }
 
-int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const void *q_win, const void *k,
+ScoreWs ws_of(fkv_ctx *ctx) {
+  ScoreWs w{};
+  w.partial = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.partial);
+  w.partial_stride = ctx->lay.max_stat_blocks;
+  w.rowstat = reinterpret_cast<float *>(ctx->ws + ctx->lay.rowstat);
+  w.fused_part = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.fused_part);
+  w.fused_lse = reinterpret_cast<float *>(ctx->ws + ctx->lay.fused_lse);
+  w.err = reinterpret_cast<unsigned *>(ctx->ws + ctx->lay.counters) + kCtrError;
+  w.n_cu = ctx->n_cu;
+  w.score_path = ctx->score_path;
+  w.wait_ticks = ctx->wait_ticks;
+  w.device = ctx->device;
+  w.prof = ctx;
+  return w;
+}
+
+int enqueue_score(const ScoreWs &w, const fkv_shape *sh, const Resolved &r, const void *q_win, const void *k,
                   float *scores_group, float *scores_tsp, float *scores_head, hipStream_t st) {
   ScoreArgs a{};
   a.q_win = static_cast<const uint16_t *>(q_win);
   a.k = static_cast<const uint16_t *>(k);
-  a.partial = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.partial);
-  a.partial_stride = ctx->lay.max_stat_blocks;
-  a.rowstat = reinterpret_cast<float *>(ctx->ws + ctx->lay.rowstat);
+  a.partial = w.partial;
+  a.partial_stride = w.partial_stride;
+  a.rowstat = w.rowstat;
   a.scores_group = scores_group;
   a.scores_tsp = scores_tsp;
   a.scores_head = scores_head;
@@ -208,7 +243,7 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
   fill_map(r, &a.map);
 
   // Single pass over K when every block of the batch can be resident at once.
-  {
+  if (w.fused_part != nullptr) {
     FusedArgs f{};
     // Fewest 32-token sub-tiles per block for which the batch still fits the resident grid: short
     // inputs then spread over more blocks and each block streams less before the grid exchange.
@@ -216,21 +251,18 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
     // sequence also computes the W window columns, so it can own fewer tokens than the others.
     const int halo_mid = 2 * a.pool_r;
     const int halo_last = a.pool_r + (a.pool_r > r.W ? a.pool_r : r.W);
-    int total = 0, clusters = 0;
+    int total = 0;
     bool fits = false;
-    // Measured over 2048 .. 32768 tokens: the exchange gets slower with the number of blocks, so a
-    // launch of more than 224 blocks (128 when a block holds a single sub-tile) loses to one more
-    // sub-tile per block.  The first round looks for a layout within those counts, the second
-    // takes whatever fits the resident grid.
+    // The first round looks for a layout within the block counts the exchange was measured to
+    // favour, the second takes whatever fits the resident grid.
     for (int round = 0; round < 2 && !fits; ++round)
-    for (int n_sub = 1; n_sub * 32 <= fused_slots() && !fits && ctx->score_path != 1 && r.V <= kMaxKvHeads; ++n_sub) {
+    for (int n_sub = 1; n_sub * 32 <= fused_slots() && !fits && w.score_path != 1 && r.V <= kMaxKvHeads; ++n_sub) {
       const int own_mid = n_sub * 32 - halo_mid, own_last = n_sub * 32 - halo_last;
       if (own_last < 1) continue;
-      const int max_blocks = round == 1 ? ctx->n_cu : std::min(ctx->n_cu, n_sub == 1 ? 128 : 224);
+      const int max_blocks = round == 1 ? w.n_cu : std::min(w.n_cu, fused_preferred_blocks(n_sub));
       fits = true;
       f.n_sub_max = n_sub;
-      total = clusters = 0;
-      f.cl0[0] = 0;
+      total = 0;
       for (int b = 0; b < r.n_seq && fits; ++b) {
         const int P = r.cu[b + 1] - r.cu[b] - r.W;
         // largest share per block (fewest blocks) whose remainder fits the last block
@@ -243,29 +275,24 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
         a.map.blk[b] = total;
         f.own[b] = own;
         total += nb_b;
-        clusters += (nb_b + fused_cluster_size() - 1) / fused_cluster_size();
-        f.cl0[b + 1] = clusters;
-        if (total > max_blocks || total > kMaxFusedBlocks || clusters > kMaxClusters) fits = false;
+        if (total > max_blocks || total > kMaxFusedBlocks) fits = false;
       }
     }
-    if (ctx->score_path == 2 && !(fits && total > 0)) return FKV_EUNSUPPORTED;
+    if (w.score_path == 2 && !(fits && total > 0)) return FKV_EUNSUPPORTED;
     if (fits && total > 0) {
       a.map.blk[r.n_seq] = total;
-      f.counters = reinterpret_cast<unsigned *>(ctx->ws + ctx->lay.counters);
-      f.bpartial = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.bpartial);
-      f.bpartial_stride = kMaxFusedBlocks;
-      f.cpartial = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.cpartial);
-      f.cpartial_stride = kMaxClusters;
+      f.part = w.fused_part;
+      f.lse = w.fused_lse;
+      f.err = w.err;
       f.n_wg = total;
-      f.n_clusters = clusters;
-      f.timeout_ticks = ctx->wait_ticks;
-      FusedGate &gate = g_gate[ctx->device & 15];
+      f.timeout_ticks = w.wait_ticks;
+      FusedGate &gate = g_gate[w.device & 15];
       std::lock_guard<std::mutex> lock(gate.mu);
       const bool chained = gate.n_ctx > 1 && gate.last != nullptr;
       hipError_t e = hipSuccess;
       if (chained && gate.recorded) e = hipStreamWaitEvent(st, gate.last, 0);
       if (e == hipSuccess) {
-        Timed t(ctx, st, KID_SCORE_FUSED);
+        Timed t(w.prof, st, KID_SCORE_FUSED);
         e = launch_score_fused(a, f, st);
       }
       if (e == hipSuccess && chained) {
@@ -275,12 +302,15 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
       return e == hipSuccess ? FKV_OK : hip_fail(e);
     }
     if (r.sum_p == 0) return FKV_OK;  // no prefix token anywhere: nothing to score
+  } else if (w.score_path == 2) {
+    return FKV_EUNSUPPORTED;
   }
+  if (r.sum_p == 0) return FKV_OK;
 
   // pass 1: softmax statistics of every window row over all L keys.  Blocks take at least
   // stats_chunk_tokens() tokens, more when that keeps the launch near one block per CU (the Q
   // load and the fold at the end of a block are paid once per block).
-  const int n_cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
+  const int n_cu = w.n_cu > 0 ? w.n_cu : 256;
   {
     const int64_t per_cu = (r.total + n_cu - 1) / n_cu;
     int chunk = (int)((per_cu + 31) / 32 * 32);
@@ -294,11 +324,11 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
     nb += (r.cu[b + 1] - r.cu[b] + a.chunk - 1) / a.chunk;
   }
   a.map.blk[r.n_seq] = nb;
-  if (nb > ctx->lay.max_stat_blocks) return FKV_EWORKSPACE;
+  if (nb > w.partial_stride) return FKV_EWORKSPACE;
   hipError_t e;
-  { Timed t(ctx, st, KID_STATS);   e = launch_stats(a, nb, st); }
+  { Timed t(w.prof, st, KID_STATS);   e = launch_stats(a, nb, st); }
   if (e != hipSuccess) return hip_fail(e);
-  { Timed t(ctx, st, KID_COMBINE); e = launch_combine(a, st); }
+  { Timed t(w.prof, st, KID_COMBINE); e = launch_combine(a, st); }
   if (e != hipSuccess) return hip_fail(e);
 
   // pass 2: scores of the prefix tokens; tiles overlap by the pooling halo
@@ -320,7 +350,7 @@ int enqueue_score(fkv_ctx *ctx, const fkv_shape *sh, const Resolved &r, const vo
   }
   a.map.blk[r.n_seq] = nb;
   if (nb > 0) {
-    Timed t(ctx, st, KID_SCORES);
+    Timed t(w.prof, st, KID_SCORES);
     e = launch_scores(a, nb, st);
     if (e != hipSuccess) return hip_fail(e);
   }
@@ -373,7 +403,10 @@ int enqueue_gather(fkv_ctx *ctx, GatherArgs &g, const Resolved &r, hipStream_t s
 }  // namespace
 
 #ifdef FKV_TIMING
-namespace fkv { __device__ unsigned long long fkv_ticks[64]; __device__ unsigned long long fkv_block_ticks[1024 * 4]; }
+namespace fkv { __device__ unsigned long long fkv_ticks[64]; __device__ unsigned long long fkv_block_ticks[1024 * 4]; __device__ unsigned long long fkv_wave_ticks[1024 * 8 * 4]; }
+extern "C" int fkv_debug_read_wave_ticks(unsigned long long *out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(fkv::fkv_wave_ticks), sizeof(unsigned long long) * 1024 * 8 * 4);
+}
 extern "C" int fkv_debug_read_block_ticks(unsigned long long *out) {
   return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(fkv::fkv_block_ticks), sizeof(unsigned long long) * 4096);
 }
@@ -424,7 +457,15 @@ int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_
   *out = nullptr;
   if (max_total_tokens < 1 || max_total_tokens > INT32_MAX || max_seqs < 1) return FKV_EINVAL;
   if (max_seqs > FKV_MAX_SEQS) return FKV_EUNSUPPORTED;
-  hipError_t e = hipSetDevice(device);
+  // the caller's current device is put back before returning
+  int caller_device = -1;
+  hipError_t e = hipGetDevice(&caller_device);
+  if (e != hipSuccess) return hip_fail(e);
+  struct RestoreDevice {
+    int dev;
+    ~RestoreDevice() { (void)hipSetDevice(dev); }
+  } restore{caller_device};
+  e = hipSetDevice(device);
   if (e != hipSuccess) return hip_fail(e);
   fkv_ctx *c = new (std::nothrow) fkv_ctx();
   if (!c) return FKV_EINVAL;
@@ -452,10 +493,16 @@ int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_
     FusedGate &gate = g_gate[device & 15];
     std::lock_guard<std::mutex> lock(gate.mu);
     if (e == hipSuccess && gate.last == nullptr) e = hipEventCreateWithFlags(&gate.last, hipEventDisableTiming);
+    // launches made while this was the device's only context carry no event: let them finish
+    // before chained launches begin
+    if (e == hipSuccess && gate.n_ctx >= 1) e = hipDeviceSynchronize();
     if (e == hipSuccess) ++gate.n_ctx;
   }
   const bool counted = e == hipSuccess;
   if (e == hipSuccess) e = hipMemset(c->ws + c->lay.counters, 0, kNumCounters * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(c->ws + c->lay.fused_part, 0xFF, kFusedPartBytes);  // every mailbox empty
+  if (e == hipSuccess) e = hipMemset(c->ws + c->lay.fused_lse, 0xFF, kFusedLseBytes);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipMemset(c->ws + c->lay.sel_long, 0, (size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
   if (e != hipSuccess) {
     if (counted) {
@@ -494,7 +541,7 @@ int fkv_score_window(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, co
   if (misaligned(q_win) || misaligned(k) || misaligned(scores_group) || misaligned(scores_tsp)) return FKV_EALIGN;
   rc = check_ctx(ctx, r);
   if (rc != FKV_OK) return rc;
-  return enqueue_score(ctx, shape, r, q_win, k, scores_group, scores_tsp, nullptr, static_cast<hipStream_t>(stream));
+  return enqueue_score(ws_of(ctx), shape, r, q_win, k, scores_group, scores_tsp, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int fkv_select_topk(fkv_ctx *ctx, const fkv_shape *shape, const float *scores, int32_t n_rows,
@@ -572,7 +619,7 @@ int fkv_score_heads(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
   if (misaligned(q_win) || misaligned(k) || misaligned(scores_head)) return FKV_EALIGN;
   rc = check_ctx(ctx, r);
   if (rc != FKV_OK) return rc;
-  return enqueue_score(ctx, shape, r, q_win, k, nullptr, nullptr, scores_head, static_cast<hipStream_t>(stream));
+  return enqueue_score(ws_of(ctx), shape, r, q_win, k, nullptr, nullptr, scores_head, static_cast<hipStream_t>(stream));
 }
 
 int fkv_gather_kv_per_head(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const void *v,
@@ -812,13 +859,14 @@ int fkv_compress_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *q_wi
   if (rc != FKV_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   float *sg = reinterpret_cast<float *>(ctx->ws + ctx->lay.scores_group);
-  rc = enqueue_score(ctx, shape, r, q_win, k, sg, nullptr, nullptr, st);
+  rc = enqueue_score(ws_of(ctx), shape, r, q_win, k, sg, nullptr, nullptr, st);
   if (rc != FKV_OK) return rc;
   SelectArgs a{};
   a.W = r.W;
   a.n_seq = r.n_seq;
   for (int b = 0; b <= r.n_seq; ++b) a.cu[b] = r.cu[b];
   a.n_sets = 0;
+  a.err = ws_of(ctx).err;
   fill_rowset(&a.set[a.n_sets++], sg, r.sum_p, r.Hkv, idx_kv, g.cnt_off, r.n_seq);
   {
     Timed t(ctx, st, KID_SELECT);
@@ -919,7 +967,7 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
   hipStream_t st = static_cast<hipStream_t>(stream);
   float *sg = reinterpret_cast<float *>(ctx->ws + ctx->lay.scores_group);
   float *stp = tsp ? reinterpret_cast<float *>(ctx->ws + ctx->lay.scores_tsp) : nullptr;
-  rc = enqueue_score(ctx, shape, r, q_win, k, sg, stp, nullptr, st);
+  rc = enqueue_score(ws_of(ctx), shape, r, q_win, k, sg, stp, nullptr, st);
   if (rc != FKV_OK) return rc;
 
   SelectArgs a{};
@@ -927,6 +975,7 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
   a.n_seq = r.n_seq;
   for (int b = 0; b <= r.n_seq; ++b) a.cu[b] = r.cu[b];
   a.n_sets = 0;
+  a.err = ws_of(ctx).err;
   fill_rowset(&a.set[a.n_sets++], sg, r.sum_p, r.Hkv, idx_kv, off_kv, r.n_seq);
   if (tsp) fill_rowset(&a.set[a.n_sets++], stp, r.sum_p, 1, idx_tsp, off_tsp, r.n_seq);
   {
@@ -954,7 +1003,9 @@ int fkv_set_score_path(fkv_ctx *ctx, int mode) {
 int fkv_query_error(fkv_ctx *ctx, int32_t *flag_out) {
   if (!ctx || !flag_out) return FKV_ENULL;
   unsigned v = 0;
-  const hipError_t e = hipMemcpy(&v, ctx->ws + ctx->lay.counters + kCtrError * sizeof(unsigned), sizeof v,
+  hipError_t e = hipDeviceSynchronize();  // streams created non-blocking do not wait for the copy below
+  if (e != hipSuccess) return hip_fail(e);
+  e = hipMemcpy(&v, ctx->ws + ctx->lay.counters + kCtrError * sizeof(unsigned), sizeof v,
                                  hipMemcpyDeviceToHost);
   if (e != hipSuccess) return hip_fail(e);
   *flag_out = (int32_t)v;
@@ -970,7 +1021,12 @@ int fkv_set_wait_limit(fkv_ctx *ctx, int64_t microseconds) {
 
 int fkv_clear_error(fkv_ctx *ctx) {
   if (!ctx) return FKV_ENULL;
-  const hipError_t e = hipMemset(ctx->ws + ctx->lay.counters + kCtrError * sizeof(unsigned), 0, sizeof(unsigned));
+  hipError_t e = hipDeviceSynchronize();
+  // a failed exchange may have left values in the mailboxes: empty them all, then drop the flag
+  if (e == hipSuccess) e = hipMemset(ctx->ws + ctx->lay.fused_part, 0xFF, kFusedPartBytes);
+  if (e == hipSuccess) e = hipMemset(ctx->ws + ctx->lay.fused_lse, 0xFF, kFusedLseBytes);
+  if (e == hipSuccess) e = hipMemset(ctx->ws + ctx->lay.counters + kCtrError * sizeof(unsigned), 0, sizeof(unsigned));
+  if (e == hipSuccess) e = hipDeviceSynchronize();
   return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 

@@ -57,4 +57,53 @@ __device__ __forceinline__ uint32_t wave_sum_to_last(uint32_t x) {
   return x;
 }
 
+// ---- fp32 variants --------------------------------------------------------------------------
+template <int kCtrl, int kRowMask = 0xF>
+__device__ __forceinline__ float dpp_f32(float old, float src) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(src), kCtrl, kRowMask, 0xF, false));
+}
+
+// Maximum / sum over the 32 lanes of each wave half (lanes 0-31 and 32-63 separately), in every lane.
+// Rotations inside the 16-lane DPP rows, then one swap of the odd and even rows.  The summation order
+// depends on the lane, so two lanes of a half may differ in the last bit: callers that need one
+// value take it from a fixed lane.
+__device__ __forceinline__ float half_max(float x) {
+  x = fmaxf(x, dpp_f32<kDppRowRor + 8>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowRor + 4>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowRor + 2>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowRor + 1>(x, x));
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+  x += dpp_f32<kDppRowRor + 8>(0.f, x);
+  x += dpp_f32<kDppRowRor + 4>(0.f, x);
+  x += dpp_f32<kDppRowRor + 2>(0.f, x);
+  x += dpp_f32<kDppRowRor + 1>(0.f, x);
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Maximum / sum over the 64 lanes as a wave-uniform value (fixed order: reproducible).
+__device__ __forceinline__ float wave_fmax(float x) {
+  x = fmaxf(x, dpp_f32<kDppRowRor + 8>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowRor + 4>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowRor + 2>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowRor + 1>(x, x));
+  x = fmaxf(x, dpp_f32<kDppBcast15, 0xA>(x, x));
+  x = fmaxf(x, dpp_f32<kDppBcast31, 0xC>(x, x));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+__device__ __forceinline__ float wave_fsum(float x) {
+  x += dpp_f32<kDppRowRor + 8>(0.f, x);
+  x += dpp_f32<kDppRowRor + 4>(0.f, x);
+  x += dpp_f32<kDppRowRor + 2>(0.f, x);
+  x += dpp_f32<kDppRowRor + 1>(0.f, x);
+  x += dpp_f32<kDppBcast15, 0xA>(0.f, x);
+  x += dpp_f32<kDppBcast31, 0xC>(0.f, x);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
 }  // namespace fkv

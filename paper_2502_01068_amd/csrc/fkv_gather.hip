@@ -9,17 +9,8 @@
 
 namespace fkv {
 
-#ifndef FKV_GATHER_THREADS
-#define FKV_GATHER_THREADS 256
-#endif
-#ifndef FKV_GATHER_UNROLL
-#define FKV_GATHER_UNROLL 2
-#endif
-#ifndef FKV_GATHER_NT
-#define FKV_GATHER_NT 1
-#endif
-constexpr int kGatherThreads = FKV_GATHER_THREADS;
-constexpr int kGatherUnroll = FKV_GATHER_UNROLL;  // 16-byte chunks in flight per thread
+constexpr int kGatherThreads = 256;
+constexpr int kGatherUnroll = 2;  // 16-byte chunks in flight per thread
 
 int gather_blocks_per_head(const GatherJob &j) {
   const int64_t chunks = (int64_t)j.total_rows * (j.row_bytes / 16);
@@ -53,23 +44,20 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather(GatherArgs a) {
       else { t = c / cpr; col = c - t * cpr; }
       int b = 0;
       while (b + 1 < a.n_seq && (int)t >= job.cnt_off[b + 1]) ++b;
-      // an index outside its sequence is clamped into it: a wrong row, never an out-of-bounds read
-      const int local = min(max(idx[t], 0), a.cu[b + 1] - a.cu[b] - 1);
+      // an index beyond its sequence is clamped into it: a wrong row, never an out-of-bounds read;
+      // a negative index (the mark of an invalid selection) copies nothing
+      const int raw = idx[t];
+      live[u] = raw >= 0;
+      const int local = min(max(raw, 0), a.cu[b + 1] - a.cu[b] - 1);
       const size_t tok = (size_t)a.cu[b] + (size_t)local;
-#if FKV_GATHER_NT
+      // rows are read once and written once: non-temporal both ways (plain stores leave the L2 dirty and
+      // measurably slow the next score launch)
       val[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src_h + tok * job.src_row_stride) + col);
-#else
-      val[u] = *(reinterpret_cast<const u32x4 *>(src_h + tok * job.src_row_stride) + col);
-#endif
     }
   }
 #pragma unroll
   for (int u = 0; u < kGatherUnroll; ++u)
-#if FKV_GATHER_NT
     if (live[u]) __builtin_nontemporal_store(val[u], dst_h + (c0 + u * kGatherThreads));
-#else
-    if (live[u]) dst_h[c0 + u * kGatherThreads] = val[u];
-#endif
 }
 
 // Paged destination: chunk c of the launch is 16 bytes of (kept slot t, KV head g), heads fastest,
@@ -95,10 +83,11 @@ __global__ __launch_bounds__(kGatherThreads) void k_gather_paged(PagedGatherArgs
       while (b + 1 < a.n_seq && (int)t >= a.cnt_off[b + 1]) ++b;
       const uint32_t tl = t - a.cnt_off[b];
       const int page = a.block_table[(size_t)b * a.max_pages + (tl >> a.page_shift)];
-      const int local = min(max(a.idx[(size_t)g * a.total_rows + t], 0), a.cu[b + 1] - a.cu[b] - 1);
+      const int raw = a.idx[(size_t)g * a.total_rows + t];
+      const int local = min(max(raw, 0), a.cu[b + 1] - a.cu[b] - 1);
       const size_t tok = (size_t)a.cu[b] + (size_t)local;
       val[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (tok * a.Hkv + g) * (kHeadDim * 2)) + col);
-      if (page >= 0 && page < a.n_pages) {
+      if (raw >= 0 && page >= 0 && page < a.n_pages) {
         const size_t slot = ((size_t)page << a.page_shift) + (tl & ((1u << a.page_shift) - 1u));
         dst[u] = reinterpret_cast<u32x4 *>(pages + (slot * a.Hkv + g) * (kHeadDim * 2)) + col;
       }

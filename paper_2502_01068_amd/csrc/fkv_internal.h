@@ -21,6 +21,7 @@ constexpr int kMaxReal = 8;       // G <= 8
 constexpr int kMaxVGroups = 16;   // Hkv * vg
 constexpr int kRowsPerGroup = 32; // MFMA M: row m = head_in_group * 8 + w
 constexpr int kMaxPoolKernel = 31;
+constexpr int kStatsChunk = 128;  // fewest tokens per block in the statistics pass of the two-pass score kernels
 
 // Phase timestamps for kernel tuning builds (-DFKV_TIMING): block (0,0), thread 0 stores the
 // 100 MHz wall clock into fkv_ticks[i].  Compiles to nothing in the product build.
@@ -39,10 +40,17 @@ extern __device__ unsigned long long fkv_block_ticks[1024 * 4];
   do {                                                                                      \
     if (threadIdx.x == 0 && (blk) < 1024) fkv::fkv_block_ticks[(blk) * 4 + (i)] = wall_clock64(); \
   } while (0)
+extern __device__ unsigned long long fkv_wave_ticks[1024 * 8 * 4];
+#define FKV_WTICK(i)                                                                        \
+  do {                                                                                      \
+    if ((threadIdx.x & 63) == 0 && blockIdx.x < 1024 && blockDim.x <= 512)                  \
+      fkv::fkv_wave_ticks[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 4 + (i)] = wall_clock64(); \
+  } while (0)
 #else
 #define FKV_TICK(i) ((void)0)
 #define FKV_BTICK(i) ((void)0)
 #define FKV_BTICK_AT(blk, i) ((void)0)
+#define FKV_WTICK(i) ((void)0)
 #endif
 #ifndef FKV_TIMING_BLOCK
 #define FKV_TIMING_BLOCK 0
@@ -81,25 +89,22 @@ struct ScoreArgs {
   int64_t sum_p;          // row stride of scores_group
 };
 
-// Single-pass (resident grid) score kernel: per-launch plan and grid-exchange buffers.
-constexpr int kMaxFusedBlocks = 512;  // upper bound on resident blocks (CUs) the exchange buffers hold
-constexpr int kMaxClusters = FKV_MAX_SEQS + 32;
-constexpr int kCtrDone = kMaxClusters, kCtrExit = kMaxClusters + 1, kCtrError = kMaxClusters + 2;
-constexpr int kNumCounters = 128;
-static_assert(kCtrError < kNumCounters, "counter block");
+// Single-pass (resident grid) score kernel: per-launch plan and the mailboxes of its grid exchange.
+constexpr int kMaxFusedBlocks = 256;  // upper bound on resident blocks (one per CU) the mailboxes hold
+constexpr int kLseRowsPerBlock = kMaxKvHeads * kRowsPerGroup;  // result boxes per block: one per softmax row
+constexpr int kCtrError = 0;          // sticky error flag of the context
+constexpr int kNumCounters = 64;
 struct FusedArgs {
-  unsigned *counters;      // [kNumCounters], zero between launches
-  float2 *bpartial;        // [Hkv*32][bpartial_stride]: per block (max, sum), log2 units
-  int bpartial_stride;
-  float2 *cpartial;        // [Hkv*32][cpartial_stride]: per cluster (max, sum)
-  int cpartial_stride;
+  float2 *part;            // [Hkv*32][kMaxFusedBlocks]: (max, sum) of a softmax row over one block's tokens, log2 units
+  float *lse;              // [kMaxFusedBlocks][kLseRowsPerBlock]: log-sum-exp of each row, one copy per block
+  unsigned *err;           // the context's sticky error flag
   int n_wg;                // blocks of the launch (all resident at once)
   int n_sub_max;           // most 32-token sub-tiles any block of the launch computes
-  int n_clusters;
-  unsigned long long timeout_ticks;  // bound of the grid wait, 100 MHz ticks
+  unsigned long long timeout_ticks;  // bound of every wait of the exchange, 100 MHz ticks
   int own[FKV_MAX_SEQS];             // prefix tokens owned by each block of sequence b
-  int cl0[FKV_MAX_SEQS + 1];         // first cluster of sequence b
 };
+constexpr size_t kFusedPartBytes = (size_t)kMaxKvHeads * kRowsPerGroup * kMaxFusedBlocks * sizeof(float2);
+constexpr size_t kFusedLseBytes = (size_t)kMaxFusedBlocks * kLseRowsPerBlock * sizeof(float);
 // Virtual-group helpers (a = any args struct with Hkv, G, vsh).
 template <typename A> __host__ __device__ inline int vg_kv_head(const A &a, int v) { return v >> a.vsh; }
 template <typename A> __host__ __device__ inline int vg_head0(const A &a, int v) {
@@ -110,7 +115,7 @@ template <typename A> __host__ __device__ inline int vg_heads(const A &a, int v)
   return left < kMaxGroup ? left : kMaxGroup;
 }
 int fused_slots(void);
-int fused_cluster_size(void);
+int fused_preferred_blocks(int n_sub);
 int score_fused_max_blocks_per_cu(void);
 hipError_t launch_score_fused(const ScoreArgs &a, const FusedArgs &f, hipStream_t s);
 
@@ -143,6 +148,8 @@ struct SelectArgs {
   int n_seq;
   int cu[FKV_MAX_SEQS + 1];
   uint32_t *long_state;  // [kLongMaxInst][kLongStateWords], or nullptr: long rows stay on the one-block kernel
+  const unsigned *err;   // sticky error flag of the score pass that produced the rows, or nullptr: while it is
+                         // set every index written is -1 (the scores are invalid)
 };
 // `long_state` is the context's state buffer for rows over 32768 keys (may be nullptr).
 hipError_t launch_select(SelectArgs a, uint32_t *long_state, hipStream_t s);

@@ -10,7 +10,6 @@ typedef __attribute__((ext_vector_type(16))) float floatx16;
 
 constexpr int kWaves = 8;            // one wave per KV head
 constexpr int kThreads = kWaves * 64;
-constexpr int kStatsChunk = 128;     // fewest tokens per block in k_stats
 constexpr int kScoresSubShort = 4;   // k_scores: sub-tiles per block (incl. pooling halo), short inputs
 constexpr int kScoresSubLong = 18;   // ... and the most for long inputs (LDS bound)
 constexpr int kScoresSubWide = 9;    // ... when more than 8 virtual groups keep their window sums in LDS
@@ -207,6 +206,31 @@ __device__ __forceinline__ void pool_and_write(const ScoreArgs &a, const float (
   const bool split = a.vsh != 0;  // a KV group spans two virtual groups: its mean is formed after the barrier
   for (int g = threadIdx.x >> 6; g < a.V; g += n_waves) {  // one wave per virtual group
     const int n_h = vg_heads(a, g), h0 = vg_head0(a, g);
+    if (r == 3) {
+      // kernel 7 (the paper's): the 7 taps of all heads of the group are independent LDS reads, in flight together
+#pragma unroll 1
+      for (int jj = lane; jj < own; jj += 64) {
+        const int c = o0 + jj - j0;  // slot of the pooled token
+        float p[kMaxGroup];
+#pragma unroll
+        for (int hl = 0; hl < kMaxGroup; ++hl) {
+          const float *row = s_head[g * kMaxGroup + (hl < n_h ? hl : 0)] + c;
+          const float v0 = row[-3], v1 = row[-2], v2 = row[-1], v3 = row[0], v4 = row[1], v5 = row[2], v6 = row[3];
+          p[hl] = is_max ? fmaxf(fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)), fmaxf(fmaxf(v4, v5), v6))
+                         : ((((((v0 + v1) + v2) + v3) + v4) + v5) + v6) * inv_k;
+        }
+        float gs = 0.f;
+#pragma unroll
+        for (int hl = 0; hl < kMaxGroup; ++hl)
+          if (hl < n_h) {
+            if (a.scores_head) a.scores_head[(size_t)(h0 + hl) * a.sum_p + col0 + o0 + jj] = p[hl];
+            gs += p[hl];
+          }
+        g_sum[g][jj] = gs;
+        if (a.scores_group && !split) a.scores_group[(size_t)g * a.sum_p + col0 + o0 + jj] = gs * inv_g;
+      }
+      continue;
+    }
 #pragma unroll 1
     for (int jj = lane; jj < own; jj += 64) {
       const int c = o0 + jj - j0;  // slot of the pooled token
@@ -215,11 +239,7 @@ __device__ __forceinline__ void pool_and_write(const ScoreArgs &a, const float (
       for (int hl = 0; hl < n_h; ++hl) {
         const float *row = s_head[g * kMaxGroup + hl] + c;
         float p;
-        if (r == 3) {
-          const float v0 = row[-3], v1 = row[-2], v2 = row[-1], v3 = row[0], v4 = row[1], v5 = row[2], v6 = row[3];
-          p = is_max ? fmaxf(fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)), fmaxf(fmaxf(v4, v5), v6))
-                     : ((((((v0 + v1) + v2) + v3) + v4) + v5) + v6) * inv_k;
-        } else if (is_max) {
+        if (is_max) {
           p = row[0];
           for (int t = -r; t <= r; ++t) p = fmaxf(p, row[t]);
         } else {

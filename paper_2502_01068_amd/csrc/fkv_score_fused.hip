@@ -9,14 +9,16 @@
 //
 //   phase 1  stream the block's K rows (owned range plus pooling halo), keep raw logits in
 //            registers, fold running (max, sum) of the owned tokens per softmax row
-//   phase 2  publish the block's partials; the last block to arrive in each cluster of 16
-//            folds the cluster; when all clusters are done every block folds the <= 16 cluster
-//            results of its sequence in a fixed order (bit-reproducible)
+//   phase 2  every block posts its 256 row partials; each softmax row has one owner wave somewhere
+//            in the grid that collects the row's partials from all blocks of the sequence, folds
+//            them in a fixed order (bit-reproducible) and posts the row's log-sum-exp to every
+//            block of the sequence
 //   phase 3  probabilities from the kept logits, window sum, LDS pooling, head means, write
 //
 // Used when the batch fits the resident grid (about 64K tokens on 256 CUs); longer inputs take
-// the two-pass kernels.  The wait in phase 2 is bounded: a block that does not see the grid
-// complete within the time limit raises the context's error flag and skips phase 3.
+// the two-pass kernels.  Every wait in phase 2 is bounded: a wave that does not get what it waits
+// for within the time limit raises the context's error flag, and its block writes NaN scores.
+#include "fkv_dpp.h"
 #include "fkv_score_common.h"
 
 namespace fkv {
@@ -24,38 +26,63 @@ namespace fkv {
 constexpr int kFusedSubShort = 5;  // sub-tiles (of 32 tokens) a block keeps in registers: the variant for inputs
 constexpr int kFusedSubLong = 8;   // that fit 5 per block carries less register-select work per logit
 constexpr int kFusedSlotsMax = kFusedSubLong * kSub;
-constexpr int kClusterSize = 16;
+constexpr int kBoxChunks = kMaxFusedBlocks / 64;  // 64-block chunks an owner wave collects
 
 int fused_slots(void) { return kFusedSlotsMax; }
-int fused_cluster_size(void) { return kClusterSize; }
+// Block count up to which a layout of n_sub sub-tiles per block is preferred over one more sub-tile
+// per block (fewer, longer blocks): swept over 2048 .. 61440 tokens.
+int fused_preferred_blocks(int n_sub) { return n_sub == 1 ? 128 : 224; }
 
-// Cross-block exchange without cache maintenance.  The L2 caches of the chip's XCDs are not
-// coherent with each other, and an agent-scope release / acquire fence writes back / invalidates
-// a whole L2 (tens of microseconds here).  Instead every value another block reads is written
-// with an agent-scope atomic exchange (performed at the coherence point, complete when its
-// result returns) and read with an agent-scope atomic load (which bypasses the local L2); a
-// workgroup-scope fence (wait for outstanding memory operations, no cache action) plus the
-// block barrier orders them before the counter update.  These buffers are touched by nothing else.
-__device__ __forceinline__ void st_coherent(float2 *p, float2 v) {
+// Cross-block exchange through mailboxes.  A mailbox slot is ONE atomic object (64 bits for a
+// (max, sum) partial, 32 bits for a log-sum-exp) that carries its own "not posted yet" state: the
+// all-ones pattern, which no posted value has.  The producer posts with a relaxed agent-scope
+// atomic exchange, the single consumer polls with relaxed agent-scope atomic loads and puts the
+// empty pattern back once it has the value.  Since the value itself is the signal, nothing has
+// to be ordered against anything else: no fences, no counters, no second location that could
+// become visible before the first (agent-scope fences would write back / invalidate a whole L2
+// on this multi-XCD part, tens of microseconds).  Each slot has one producer and one consumer per
+// launch; the empty pattern the consumer leaves behind is ordered before the next launch by the
+// kernel boundary.  Slots are touched by nothing else.
+constexpr unsigned long long kEmpty64 = ~0ull;
+constexpr unsigned kEmpty32 = ~0u;
+
+__device__ __forceinline__ void box_post(float2 *slot, float2 v) {
   unsigned long long bits;
   __builtin_memcpy(&bits, &v, sizeof bits);
-  const unsigned long long old = __hip_atomic_exchange(reinterpret_cast<unsigned long long *>(p), bits,
-                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  asm volatile("" ::"v"(old));  // keep the returning form: its completion is what the fence waits for
+  if (bits == kEmpty64) bits = 0x7FC000007FC00000ull;  // a NaN pair with that payload is posted as plain NaNs
+  (void)__hip_atomic_exchange(reinterpret_cast<unsigned long long *>(slot), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float2 ld_coherent(const float2 *p) {
-  const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
-                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  float2 v;
-  __builtin_memcpy(&v, &bits, sizeof v);
-  return v;
+__device__ __forceinline__ unsigned long long box_peek(const float2 *slot) {
+  return __hip_atomic_load(reinterpret_cast<const unsigned long long *>(slot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ unsigned ld_counter(const unsigned *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void box_clear(float2 *slot) {
+  __hip_atomic_store(reinterpret_cast<unsigned long long *>(slot), kEmpty64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void block_publish() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __syncthreads();
+__device__ __forceinline__ void box_post(float *slot, float v) {
+  unsigned bits = __float_as_uint(v);
+  if (bits == kEmpty32) bits = 0x7FC00000u;
+  (void)__hip_atomic_exchange(reinterpret_cast<unsigned *>(slot), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned box_peek(const float *slot) {
+  return __hip_atomic_load(reinterpret_cast<const unsigned *>(slot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void box_clear(float *slot) {
+  __hip_atomic_store(reinterpret_cast<unsigned *>(slot), kEmpty32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Writes NaN into every score this block owns: a call whose exchange failed must not leave
+// plausible numbers behind.
+__device__ __forceinline__ void poison_scores(const ScoreArgs &a, int col0, int o0, int o1) {
+  const float nan = __uint_as_float(0x7FC00000u);
+  const int own = o1 - o0;
+  for (int i = threadIdx.x; i < own; i += blockDim.x) {
+    const size_t col = (size_t)col0 + o0 + i;
+    if (a.scores_group)
+      for (int g = 0; g < a.Hkv; ++g) a.scores_group[(size_t)g * a.sum_p + col] = nan;
+    if (a.scores_head)
+      for (int h = 0; h < a.Hq; ++h) a.scores_head[(size_t)h * a.sum_p + col] = nan;
+    if (a.scores_tsp) a.scores_tsp[col] = nan;
+  }
 }
 
 template <int kFusedSub>
@@ -63,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   constexpr int kFusedSlots = kFusedSub * kSub;
   __shared__ __attribute__((aligned(16))) uint8_t lds_all[kWaves * kStageBytes];
   __shared__ float cst_lds[kWaves][kRowsPerGroup];
-  __shared__ unsigned flag_lds[2];
+  __shared__ unsigned flag_lds[1];
   float(*s_head)[kFusedSlots] = reinterpret_cast<float(*)[kFusedSlots]>(lds_all);  // [Hkv*4][slots]
   float(*g_sum)[kFusedSlots] =
       reinterpret_cast<float(*)[kFusedSlots]>(lds_all + kMaxKvHeads * kMaxGroup * kFusedSlots * 4);
@@ -83,15 +110,23 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   const int c0 = o0 - r;                                        // first computed token (may be < 0)
   const int c1 = last ? max(Lb, o1 + r) : o1 + r;               // the pooling halo may reach past the window (r > W)
   const int n_sub = (c1 - c0 + kSub - 1) / kSub;                // <= kFusedSub (host guarantees)
+  const int col0 = tok_base - b * a.W;
   uint8_t *stage = lds_all + wave * kStageBytes;
   const int g = wave;
   const bool has_group = g < a.V;  // the host takes this kernel only for V <= 8 (one wave per virtual group)
+
+  // A failed exchange leaves mailboxes in an unknown state: until the host has reset them
+  // (fkv_clear_error) every launch only marks its scores invalid.
+  if (*f.err != 0u) {
+    poison_scores(a, col0, o0, o1);
+    return;
+  }
+  if (threadIdx.x == 0) flag_lds[0] = 1u;
 
   FKV_TICK(32);
   FKV_BTICK(0);
   // ---- phase 1: logits into registers, running statistics of the owned tokens
   float z[kFusedSub][16], mloc[16];
-  float2 ms = make_float2(kNegBig, 0.f);
   if (has_group) {
     bf16x8 qa[8];
     load_q(a, b, g, lane, qa);
@@ -101,6 +136,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
     stream_head_direct(a, qa, tok_base, Lb, g, c0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
       const int tok = c0 + st * kSub + n;
       const bool counted = (tok >= o0 && tok < o1) || (last && tok >= P && tok < Lb);
+      const bool scored = tok >= 0 && tok < P;  // a prefix token (owned or halo): its probability is formed in phase 3
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const int w = hi * 4 + (q & 3);
@@ -109,23 +145,96 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
 #pragma unroll
         for (int t = 0; t < kFusedSub; ++t)
           if (t == st) z[t][q] = zz;
-        // running reference = max over every computed logit (counted or not), so that
-        // 2^(z - reference) <= 1 for all of them; only counted keys enter the sum
-        const float d = zz - mx[q];
+        // running reference = max over every logit that is counted or later scored, so that
+        // 2^(z - reference) <= 1 for all of them; only counted keys enter the sum.  Masked window
+        // keys and clamped slots outside the sequence are neither: they must not move the reference.
+        const float zr = (ok || scored) ? zz : kNegBig;
+        const float d = zr - mx[q];
         const float e = fast_exp2(-fabsf(d));
         const float one = ok ? 1.f : 0.f;
         sm[q] = d > 0.f ? sm[q] * e + one : sm[q] + one * e;
-        mx[q] = fmaxf(mx[q], zz);
+        mx[q] = fmaxf(mx[q], zr);
       }
     });
     FKV_TICK(33);
-    ms = fold_rows(mx, sm, reinterpret_cast<float *>(stage), lane);
-    if (lane < 32) st_coherent(f.bpartial + (size_t)(g * kRowsPerGroup + lane) * f.bpartial_stride + blockIdx.x, ms);
-    // While the exchange is in flight: turn the kept logits into 2^(z - block reference).  The
-    // global normaliser then costs one multiply per value instead of an exponential.
-    const float *mrow = reinterpret_cast<const float *>(stage) + kFoldMaxOffset;
+    FKV_WTICK(0);
+    // fold over the 32 token lanes of each wave half: registers only
+    float srow[16];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) mloc[q] = mrow[(q >> 2) * 8 + hi * 4 + (q & 3)];
+    for (int q = 0; q < 16; ++q) mloc[q] = half_max(mx[q]);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) srow[q] = half_sum(sm[q] * fast_exp2(mx[q] - mloc[q]));
+    // lanes 0-15 post the 16 rows of the low half, lanes 32-47 those of the high half
+    float pm = mloc[0], ps = srow[0];
+#pragma unroll
+    for (int q = 1; q < 16; ++q)
+      if ((lane & 15) == q) { pm = mloc[q]; ps = srow[q]; }
+    if ((lane & 31) < 16) {
+      const int q = lane & 15;
+      const int row = g * kRowsPerGroup + (q >> 2) * 8 + hi * 4 + (q & 3);
+      box_post(f.part + (size_t)row * kMaxFusedBlocks + blockIdx.x, make_float2(pm, ps));
+    }
+  }
+  FKV_TICK(34);
+  FKV_BTICK(1);
+  FKV_WTICK(1);
+
+  // ---- phase 2a: owner duty.  Softmax row t = (sequence, row) belongs to block t mod n_wg; a block
+  // spreads its rows over its waves.  The owner collects the row's partial from every block of the
+  // sequence, folds them and posts the log-sum-exp into each of those blocks' result boxes.
+  bool wave_ok = true;
+  {
+    const int rows_per_seq = a.V * kRowsPerGroup;
+    const int n_tasks = a.map.n_seq * rows_per_seq;
+    for (int t = (int)blockIdx.x + wave * f.n_wg; t < n_tasks; t += kWaves * f.n_wg) {
+      const int tb = t / rows_per_seq, row = t - tb * rows_per_seq;
+      const int blk0 = a.map.blk[tb], nb = a.map.blk[tb + 1] - blk0;
+      float2 *src = f.part + (size_t)row * kMaxFusedBlocks + blk0;
+      const int n_it = (nb + 63) >> 6;
+      unsigned long long v[kBoxChunks];
+#pragma unroll
+      for (int i = 0; i < kBoxChunks; ++i) v[i] = kEmpty64;
+      const unsigned long long t0 = wall_clock64();
+      while (true) {
+        bool missing = false;
+#pragma unroll
+        for (int i = 0; i < kBoxChunks; ++i)
+          if (i < n_it && i * 64 + lane < nb && v[i] == kEmpty64) v[i] = box_peek(src + i * 64 + lane);
+#pragma unroll
+        for (int i = 0; i < kBoxChunks; ++i)
+          if (i < n_it && i * 64 + lane < nb && v[i] == kEmpty64) missing = true;
+        if (!__any(missing)) break;
+        if (wall_clock64() - t0 > f.timeout_ticks) { wave_ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      if (!wave_ok) break;
+      float m = kNegBig, s = 0.f;
+#pragma unroll
+      for (int i = 0; i < kBoxChunks; ++i)
+        if (i < n_it && i * 64 + lane < nb) {
+          box_clear(src + i * 64 + lane);
+          float2 pv;
+          __builtin_memcpy(&pv, &v[i], sizeof pv);
+          const float mn = fmaxf(m, pv.x);
+          s = s * fast_exp2(m - mn) + pv.y * fast_exp2(pv.x - mn);
+          m = mn;
+        }
+      const float mw = wave_fmax(m);
+      const float sw = wave_fsum(s * fast_exp2(m - mw));
+      const int vg = row >> 5, rr = row & 31;
+      const bool row_ok = (rr >> 3) < vg_heads(a, vg) && (rr & 7) < a.W;
+      const float lse = row_ok ? mw + __log2f(sw) : 0.f;
+#pragma unroll
+      for (int i = 0; i < kBoxChunks; ++i)
+        if (i < n_it && i * 64 + lane < nb) box_post(f.lse + (size_t)(blk0 + i * 64 + lane) * kLseRowsPerBlock + row, lse);
+    }
+  }
+  FKV_TICK(35);
+  FKV_WTICK(2);
+
+  // While the exchange is in flight: turn the kept logits into 2^(z - block reference).  The
+  // global normaliser then costs one multiply per value instead of an exponential.
+  if (has_group) {
 #pragma unroll
     for (int st = 0; st < kFusedSub; ++st)
       if (st < n_sub) {
@@ -133,83 +242,32 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
         for (int q = 0; q < 16; ++q) z[st][q] = fast_exp2(z[st][q] - mloc[q]);
       }
   }
-
-  FKV_TICK(34);
-  FKV_BTICK(1);
-  // ---- phase 2: grid-wide fold of the row statistics
-  const int cl_local = local / kClusterSize;
-  const int cluster = f.cl0[b] + cl_local;
-  const int cl_first = a.map.blk[b] + cl_local * kClusterSize;  // first block of the cluster
-  const int cl_size = min(kClusterSize, n_ranges - cl_local * kClusterSize);
-  block_publish();
-  FKV_TICK(35);
-  if (threadIdx.x == 0) {
-    const unsigned ticket =
-        __hip_atomic_fetch_add(&f.counters[cluster], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    flag_lds[0] = (ticket == (unsigned)cl_size - 1u) ? 1u : 0u;
-  }
-  __syncthreads();
-  if (flag_lds[0]) {  // this block closes its cluster
-    if ((int)threadIdx.x < a.V * kRowsPerGroup) {
-      const float2 *src = f.bpartial + (size_t)threadIdx.x * f.bpartial_stride + cl_first;
-      float2 v[kClusterSize];  // all loads in flight before the (ordered) fold
-#pragma unroll
-      for (int i = 0; i < kClusterSize; ++i) v[i] = ld_coherent(src + (i < cl_size ? i : 0));
-      float2 acc = v[0];
-#pragma unroll
-      for (int i = 1; i < kClusterSize; ++i)
-        if (i < cl_size) acc = merge_stats(acc, v[i]);
-      st_coherent(f.cpartial + (size_t)threadIdx.x * f.cpartial_stride + cluster, acc);
-    }
-    block_publish();
-    if (threadIdx.x == 0) {
-      __hip_atomic_store(&f.counters[cluster], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_fetch_add(&f.counters[kCtrDone], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-  }
   FKV_TICK(36);
-  if (threadIdx.x == 0) {
-    const unsigned long long t0 = wall_clock64();
-    unsigned ok = 1u;
-    while (ld_counter(&f.counters[kCtrDone]) < (unsigned)f.n_clusters) {
-      __builtin_amdgcn_s_sleep(2);
-      if (wall_clock64() - t0 > f.timeout_ticks) { ok = 0u; break; }
-    }
-    flag_lds[1] = ok;
-  }
-  __syncthreads();
-  const bool grid_ok = flag_lds[1] != 0u;
-  FKV_TICK(37);
-  FKV_BTICK(2);
-  FKV_TICK(38);
 
-  if (grid_ok && has_group) {
-    // lanes l and l+32 fold the even / odd clusters of this sequence for row l, then merge
-    const int row = lane & 31, half = lane >> 5;
-    const float2 *src = f.cpartial + (size_t)(g * kRowsPerGroup + row) * f.cpartial_stride;
-    float2 acc = make_float2(kNegBig, 0.f);
-    const int c_lo = f.cl0[b] + half, c_hi = f.cl0[b + 1];
-    for (int cb = c_lo; cb < c_hi; cb += 16) {  // 8 loads in flight per round, folded in order
-      float2 v[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = ld_coherent(src + (cb + 2 * i < c_hi ? cb + 2 * i : c_lo));
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        if (cb + 2 * i < c_hi) acc = merge_stats(acc, v[i]);
+  // ---- phase 2b: collect the log-sum-exp of this wave's 32 rows from the block's result box
+  if (has_group && wave_ok) {
+    float *box = f.lse + (size_t)blockIdx.x * kLseRowsPerBlock + g * kRowsPerGroup + (lane & 31);
+    unsigned bits = kEmpty32;
+    const unsigned long long t0 = wall_clock64();
+    while (true) {
+      if (lane < 32 && bits == kEmpty32) bits = box_peek(box);
+      if (!__any(lane < 32 && bits == kEmpty32)) break;
+      if (wall_clock64() - t0 > f.timeout_ticks) { wave_ok = false; break; }
+      __builtin_amdgcn_s_sleep(1);
     }
-    float2 oth;
-    oth.x = __shfl_xor(acc.x, 32);
-    oth.y = __shfl_xor(acc.y, 32);
-    const float2 lo2 = half ? oth : acc, hi2 = half ? acc : oth;
-    const float2 tot = merge_stats(lo2, hi2);
-    const bool row_ok = (row >> 3) < vg_heads(a, g) && (row & 7) < a.W;
-    if (lane < 32) cst_lds[wave][row] = row_ok ? (tot.x + __log2f(tot.y)) : 0.f;
+    if (wave_ok && lane < 32) {
+      box_clear(box);
+      cst_lds[wave][lane] = __uint_as_float(bits);
+    }
   }
-  __syncthreads();  // all staging tiles are dead, cst_lds is visible
-  FKV_TICK(39);
+  FKV_BTICK(2);
+  FKV_WTICK(3);
+  __syncthreads();  // every wave has left its staging tile (phase 3 reuses them); flag_lds is initialised
+  if (!wave_ok && lane == 0) flag_lds[0] = 0u;
+  FKV_TICK(37);
 
   // ---- phase 3: probabilities from the kept logits, window sums into LDS
-  if (grid_ok && has_group) {
+  if (has_group && wave_ok) {
     float fac[16];  // 2^(block reference - global log-sum-exp) per row
 #pragma unroll
     for (int q = 0; q < 16; ++q) fac[q] = fast_exp2(mloc[q] - cst_lds[wave][(q >> 2) * 8 + hi * 4 + (q & 3)]);
@@ -231,19 +289,15 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   }
   __syncthreads();
   FKV_TICK(40);
-  if (grid_ok) pool_and_write<kFusedSlots>(a, s_head, g_sum, c0, o0, o1, tok_base - b * a.W);
+  const bool grid_ok = flag_lds[0] != 0u;
+  if (grid_ok) {
+    pool_and_write<kFusedSlots>(a, s_head, g_sum, c0, o0, o1, col0);
+  } else {
+    poison_scores(a, col0, o0, o1);
+    if (threadIdx.x == 0) __hip_atomic_store(f.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   FKV_TICK(41);
   FKV_BTICK(3);
-
-  // ---- leave the grid: the last block out re-arms the counters for the next launch
-  if (threadIdx.x == 0) {
-    if (!grid_ok) __hip_atomic_store(&f.counters[kCtrError], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned e = __hip_atomic_fetch_add(&f.counters[kCtrExit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (e == (unsigned)f.n_wg - 1u) {
-      __hip_atomic_store(&f.counters[kCtrDone], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(&f.counters[kCtrExit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-  }
 }
 
 hipError_t launch_score_fused(const ScoreArgs &a, const FusedArgs &f, hipStream_t s) {

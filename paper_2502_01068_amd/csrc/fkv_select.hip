@@ -193,6 +193,10 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
   int32_t *out = rs.idx_out + (size_t)row * rs.cnt_off[a.n_seq] + rs.cnt_off[b];
 
   if (a.long_state != nullptr && P + 3 > kSelThreads * kMaxKpt) return;  // taken by the multi-block chain
+  if (a.err != nullptr && *a.err != 0u) {  // the scores are invalid: no index may look usable
+    for (int i = threadIdx.x; i < k; i += kSelThreads) out[i] = -1;
+    return;
+  }
   if ((int)threadIdx.x < a.W) out[kp + threadIdx.x] = P + threadIdx.x;  // window tokens are always kept
   if (kp <= 0) return;
   if (P + 3 <= kSelThreads * 8)

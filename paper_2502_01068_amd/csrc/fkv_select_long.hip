@@ -197,8 +197,19 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_long_compact(SelectArgs a) 
   __shared__ uint32_t sink[64];
   __shared__ uint32_t pre[2];
   const LongRow r = locate_long(a);
-  if (!r.active) return;
+  if (!r.is_long) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (a.err != nullptr && *a.err != 0u) {  // the scores are invalid: no index may look usable
+    if (r.slice == 0) {
+      for (int i = tid; i < r.kp + r.W; i += kSelThreads) r.out[i] = -1;
+      if (tid == 0) {
+        r.st[kLongInfo + kInfMax] = 0u;
+        r.st[kLongInfo + kInfNotMin] = 0u;
+      }
+    }
+    return;
+  }
+  if (!r.active) return;
   uint32_t key[kLongKpt];
   load_keys<kLongKpt>(r.base, r.mis, r.P, r.slice * kLongChunk, wave, lane, key);
   if (tid < 2) pre[tid] = 0;

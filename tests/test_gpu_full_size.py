@@ -76,7 +76,7 @@ def test_config3_128k():
     _full_check(131072, 26214, 13107, "avg", seed=0)
 
 
-@pytest.mark.parametrize("budget", [512, 2048])
+@pytest.mark.parametrize("budget", [512, 1024, 2048])
 def test_config4_ragged(budget):
     lengths = wl.ragged_lengths(0)
     print("case: config4 ragged %s budget %d" % (lengths, budget), flush=True)

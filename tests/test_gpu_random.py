@@ -180,11 +180,15 @@ def test_random_medium_batches_scores(ctx, case):
         col += P
 
 
-def test_gather_clamps_indices_outside_the_sequence(ctx):
+def test_gather_clamps_or_skips_indices_outside_the_sequence(ctx):
     print("case: gather with out-of-range indices", flush=True)
     lengths, ks = [100, 60], [8, 8]
     x = np.arange(160 * 8, dtype=np.uint16).reshape(160, 8)
     idx = np.array([0, 5, 99, 100, 2 ** 30, -1, -2 ** 31, 50, 0, 59, 60, 61, 10 ** 9, -5, 1, 2], np.int32)
-    out = host_bits(ctx.fkv_gather_rows(fk.make_shape(lengths), dev_bf16(x), torch.from_numpy(idx).cuda(), ks))
+    # an index beyond the sequence is clamped into it; a negative index (the mark of an invalid selection)
+    # copies nothing, so those output rows keep what they held
+    buf = torch.full((16, 8), 0x7777, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    out = host_bits(ctx.fkv_gather_rows(fk.make_shape(lengths), dev_bf16(x), torch.from_numpy(idx).cuda(), ks, out=buf))
     want = np.concatenate([x[np.clip(idx[:8], 0, 99)], x[100 + np.clip(idx[8:], 0, 59)]])
+    want[idx < 0] = 0x7777
     np.testing.assert_array_equal(out, want)
