@@ -276,6 +276,15 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
  * the same scores up to fp32 summation order. */
 int fkv_set_score_path(fkv_ctx *ctx, int mode);
 
+/* How the single-pass score kernel would lay a batch out over at most max_blocks resident blocks
+ * (host only; the library plans with the device's compute-unit count).  Block i of sequence b owns the
+ * prefix tokens [i * own[b], min(P_b, (i + 1) * own[b])) and computes them plus pool_kernel / 2 halo
+ * tokens on each side (the last block of a sequence: plus the W window columns instead of the right
+ * halo when W is larger).  first_block [B + 1]: first block of each sequence, first_block[B] = blocks
+ * in all; own [B]; n_sub_max: 32-token sub-tiles the largest block computes (at most 8).
+ * FKV_EUNSUPPORTED if the batch does not fit (then the two-pass kernels run). */
+int fkv_score_plan(const fkv_shape *shape, int32_t max_blocks, int32_t *first_block, int32_t *own, int32_t *n_sub_max);
+
 /* Synchronises the device (hipDeviceSynchronize) and reports the context's sticky error flag: 0, or
  * 1 if a wave of the single-pass score kernel gave up waiting for the rest of its grid (2 s bound).
  * Cannot happen while the library's launches are the only work competing for the device's compute

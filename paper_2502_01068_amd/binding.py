@@ -24,6 +24,7 @@ EXPORTS = [
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
     "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error", "fkv_compress_kv_paged", "fkv_probe_logits", "fkv_window_output",
+    "fkv_score_plan",
 ]
 
 
@@ -72,6 +73,7 @@ def load():
     lib.fkv_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i32]
     lib.fkv_destroy.argtypes = [vp]
     lib.fkv_score_window.argtypes = [vp, shp, vp, vp, vp, vp, vp]
+    lib.fkv_score_plan.argtypes = [shp, i32, pi32, pi32, pi32]
     lib.fkv_select_topk.argtypes = [vp, shp, vp, i32, pi32, vp, vp]
     lib.fkv_gather_rows.argtypes = [vp, shp, vp, sz, vp, pi32, vp, vp]
     lib.fkv_gather_kv.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
@@ -135,6 +137,19 @@ def make_shape(lengths, n_q_heads=32, n_kv_heads=8, head_dim=128, window=8, pool
 def fkv_count_from_rate(n_tokens, rate):
     """Round-half-up keep count for a rate (host only)."""
     return int(load().fkv_count_from_rate(int(n_tokens), float(rate)))
+
+
+def fkv_score_plan(shape, max_blocks=256):
+    """Block layout of the single-pass score kernel -> (first_block [B+1], own [B], n_sub_max), or None if
+    the batch does not fit max_blocks resident blocks (host only)."""
+    first = (ctypes.c_int32 * (shape.n_seq + 1))()
+    own = (ctypes.c_int32 * shape.n_seq)()
+    n_sub = ctypes.c_int32(0)
+    rc = load().fkv_score_plan(ctypes.byref(shape), int(max_blocks), first, own, ctypes.byref(n_sub))
+    if rc == FKV_EUNSUPPORTED:
+        return None
+    _check(rc, "fkv_score_plan")
+    return list(first), list(own), int(n_sub.value)
 
 
 def fkv_plan_layer(layer, n_layers, tsp_layer, n_tokens, tsp_rate, kv_rate, window=8):

@@ -205,6 +205,63 @@ void fill_map(const Resolved &r, SeqMap *m) {
   for (int b = 0; b <= r.n_seq; ++b) m->cu[b] = r.cu[b];
 }
 
+// Token ranges of the single-pass score kernel's resident grid.  Block i of sequence b owns the prefix
+// tokens [i * own[b], min(P_b, (i + 1) * own[b])) and computes them plus the pooling halo of r tokens on
+// both sides; the last block of a sequence also computes the W window columns, so for the same amount
+// of work it owns max(0, W - r) tokens fewer.  A CU streams K at a fixed rate, so the time of the pass
+// follows the most tokens any block computes; the share found below is evened out inside each sequence.  blk[b] = first
+// block of sequence b (blk[n_seq] = blocks in all), n_sub_max = 32-token sub-tiles the largest block
+// computes.  False if no layout fits (more than fused_slots() computed tokens per block needed).
+bool plan_fused(const Resolved &r, int pool_r, int max_blocks, int *blk, int *own, int *n_sub_max) {
+  const int last_less = r.W > pool_r ? r.W - pool_r : 0;
+  const int own_cap = fused_slots() - 2 * pool_r;
+  if (own_cap <= last_less || max_blocks < 1) return false;
+  // fewest blocks of a sequence at a share of at most `share` tokens per block, and the share they get:
+  // the largest o <= share whose remainder P - (nb - 1) o fits the last block
+  auto layout = [&](int P, int share, int *own_out) {
+    *own_out = 1;
+    if (P <= 0) return 0;
+    for (int o = share; o > last_less; --o) {
+      const int nb = (P + o - 1) / o;
+      if (P - (nb - 1) * o <= o - last_less) { *own_out = o; return nb; }
+    }
+    return 1 << 20;  // no layout at this share
+  };
+  auto need = [&](int share) {
+    int64_t t = 0;
+    int o;
+    for (int b = 0; b < r.n_seq; ++b) t += layout(r.cu[b + 1] - r.cu[b] - r.W, share, &o);
+    return t;
+  };
+  if (need(own_cap) > max_blocks) return false;
+  // First choice: the fewest full sub-tiles per block whose block count stays within what the grid
+  // exchange was measured to favour.  Otherwise the smallest share that fits max_blocks (the blocks
+  // needed fall as the share grows: bisect).
+  int lo = 0;
+  for (int n_sub = 1; n_sub * 32 <= fused_slots() && lo == 0; ++n_sub) {
+    const int share = n_sub * 32 - 2 * pool_r;
+    if (share > last_less && need(share) <= std::min(max_blocks, fused_preferred_blocks(n_sub))) lo = share;
+  }
+  if (lo == 0) {
+    int hi = own_cap;
+    lo = last_less + 1;
+    while (lo < hi) {
+      const int mid = (lo + hi) / 2;
+      if (need(mid) <= max_blocks) hi = mid; else lo = mid + 1;
+    }
+  }
+  int total = 0, own_max = 0;
+  for (int b = 0; b < r.n_seq; ++b) {
+    blk[b] = total;
+    total += layout(r.cu[b + 1] - r.cu[b] - r.W, lo, &own[b]);
+    if (own[b] > own_max) own_max = own[b];
+  }
+  blk[r.n_seq] = total;
+  if (total < 1 || total > max_blocks) return false;
+  *n_sub_max = (own_max + 2 * pool_r + 31) / 32;
+  return true;
+}
+
 ScoreWs ws_of(fkv_ctx *ctx) {
   ScoreWs w{};
   w.partial = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.partial);
@@ -245,42 +302,12 @@ int enqueue_score(const ScoreWs &w, const fkv_shape *sh, const Resolved &r, cons
   // Single pass over K when every block of the batch can be resident at once.
   if (w.fused_part != nullptr) {
     FusedArgs f{};
-    // Fewest 32-token sub-tiles per block for which the batch still fits the resident grid: short
-    // inputs then spread over more blocks and each block streams less before the grid exchange.
-    // A block computes its owned tokens plus the pooling halo on both sides; the last block of a
-    // sequence also computes the W window columns, so it can own fewer tokens than the others.
-    const int halo_mid = 2 * a.pool_r;
-    const int halo_last = a.pool_r + (a.pool_r > r.W ? a.pool_r : r.W);
     int total = 0;
-    bool fits = false;
-    // The first round looks for a layout within the block counts the exchange was measured to
-    // favour, the second takes whatever fits the resident grid.
-    for (int round = 0; round < 2 && !fits; ++round)
-    for (int n_sub = 1; n_sub * 32 <= fused_slots() && !fits && w.score_path != 1 && r.V <= kMaxKvHeads; ++n_sub) {
-      const int own_mid = n_sub * 32 - halo_mid, own_last = n_sub * 32 - halo_last;
-      if (own_last < 1) continue;
-      const int max_blocks = round == 1 ? w.n_cu : std::min(w.n_cu, fused_preferred_blocks(n_sub));
-      fits = true;
-      f.n_sub_max = n_sub;
-      total = 0;
-      for (int b = 0; b < r.n_seq && fits; ++b) {
-        const int P = r.cu[b + 1] - r.cu[b] - r.W;
-        // largest share per block (fewest blocks) whose remainder fits the last block
-        int own = 0, nb_b = 0;
-        for (int o = own_mid; o >= 1 && P > 0; --o) {
-          const int nb = (P + o - 1) / o;
-          if (P - (nb - 1) * o <= own_last) { own = o; nb_b = nb; break; }
-        }
-        if (P > 0 && nb_b == 0) { fits = false; break; }
-        a.map.blk[b] = total;
-        f.own[b] = own;
-        total += nb_b;
-        if (total > max_blocks || total > kMaxFusedBlocks) fits = false;
-      }
-    }
+    const bool fits = w.score_path != 1 && r.V <= kMaxKvHeads &&
+                      plan_fused(r, a.pool_r, std::min(w.n_cu, kMaxFusedBlocks), a.map.blk, f.own, &f.n_sub_max);
+    if (fits) total = a.map.blk[r.n_seq];
     if (w.score_path == 2 && !(fits && total > 0)) return FKV_EUNSUPPORTED;
     if (fits && total > 0) {
-      a.map.blk[r.n_seq] = total;
       f.part = w.fused_part;
       f.lse = w.fused_lse;
       f.err = w.err;
@@ -642,6 +669,21 @@ int fkv_gather_kv_per_head(fkv_ctx *ctx, const fkv_shape *shape, const void *k, 
   fill_job(&g.job[g.n_jobs++], k, k_out, idx_head, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hq, off, r.n_seq, r.G);
   if (v) fill_job(&g.job[g.n_jobs++], v, v_out, idx_head, (int64_t)r.Hkv * row_bytes, row_bytes, r.Hq, off, r.n_seq, r.G);
   return enqueue_gather(ctx, g, r, static_cast<hipStream_t>(stream));
+}
+
+int fkv_score_plan(const fkv_shape *shape, int32_t max_blocks, int32_t *first_block, int32_t *own, int32_t *n_sub_max) {
+  Resolved r;
+  const int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!first_block || !own || !n_sub_max) return FKV_ENULL;
+  if (max_blocks < 1) return FKV_EINVAL;
+  int blk[FKV_MAX_SEQS + 1], o[FKV_MAX_SEQS], ns = 0;
+  if (r.V > kMaxKvHeads || !plan_fused(r, shape->pool_kernel / 2, std::min(max_blocks, kMaxFusedBlocks), blk, o, &ns))
+    return FKV_EUNSUPPORTED;
+  for (int b = 0; b <= r.n_seq; ++b) first_block[b] = blk[b];
+  for (int b = 0; b < r.n_seq; ++b) own[b] = o[b];
+  *n_sub_max = ns;
+  return FKV_OK;
 }
 
 int32_t fkv_count_from_rate(int32_t n_tokens, double rate) {

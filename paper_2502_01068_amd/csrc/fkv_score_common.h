@@ -103,9 +103,13 @@ __device__ __forceinline__ void stream_head(const ScoreArgs &a, const bf16x8 (&q
 // side: the lane that owns LDS column c' of token slot t fetches the row's column c' ^ (t & 15).
 // Per sub-tile: wait for its loads, run the MFMAs off the tile, start the next sub-tile's loads into
 // the same (now free) tile, run fn while they are in flight.
+// Only the first n_slots token slots (counted from `first`) are loaded: the rest of the last sub-tile
+// keeps whatever the LDS tile held, and the caller ignores those tokens' logits (they may be anything,
+// NaN included; a token is one MFMA column, so nothing spreads to other tokens).
 template <typename F>
 __device__ __forceinline__ void stream_head_direct(const ScoreArgs &a, const bf16x8 (&qa)[8], int tok_base, int Lb,
-                                                   int g, int first, int n_sub, uint8_t *stage, int lane, F fn) {
+                                                   int g, int first, int n_slots, uint8_t *stage, int lane, F fn) {
+  const int n_sub = (n_slots + kSub - 1) / kSub;
   const int c = lane & 15;        // LDS column of this lane within a token slot
   const int tq = lane >> 4;       // token within the quad of 4 tokens one load instruction covers
   const int n = lane & 31, hi = lane >> 5;
@@ -117,6 +121,7 @@ __device__ __forceinline__ void stream_head_direct(const ScoreArgs &a, const bf1
   auto issue = [&](int st) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
+      if (st * kSub + i * 4 >= n_slots) break;  // wave-uniform: this instruction's 4 tokens are all beyond the range
       const int slot = i * 4 + tq;
       int t = first + st * kSub + slot;
       t = min(max(t, 0), Lb - 1);

@@ -29,8 +29,10 @@ constexpr int kFusedSlotsMax = kFusedSubLong * kSub;
 constexpr int kBoxChunks = kMaxFusedBlocks / 64;  // 64-block chunks an owner wave collects
 
 int fused_slots(void) { return kFusedSlotsMax; }
-// Block count up to which a layout of n_sub sub-tiles per block is preferred over one more sub-tile
-// per block (fewer, longer blocks): swept over 2048 .. 61440 tokens.
+// Block count up to which a layout of n_sub full sub-tiles per block is preferred over one more
+// sub-tile per block (fewer, longer blocks): the exchange gets slower with the number of blocks.
+// Swept over 2048 .. 49152 tokens (e.g. 6554 tokens: 64 blocks 21.1 us, 113 blocks 18.0, 160 blocks
+// 18.6, 256 blocks 18.4; 32768 tokens: 213 blocks 28.3, 256 blocks 28.7).
 int fused_preferred_blocks(int n_sub) { return n_sub == 1 ? 128 : 224; }
 
 // Cross-block exchange through mailboxes.  A mailbox slot is ONE atomic object (64 bits for a
@@ -69,6 +71,29 @@ __device__ __forceinline__ unsigned box_peek(const float *slot) {
 __device__ __forceinline__ void box_clear(float *slot) {
   __hip_atomic_store(reinterpret_cast<unsigned *>(slot), kEmpty32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+
+// Time limit of a polling loop.  Reading the clock costs a round trip through the scalar memory path
+// (comparable to the poll itself), so it is read only every 64th round, the first time to start
+// the interval; limits below 1 ms (how tests force the failure path) are checked on every round,
+// from a start time taken before the first poll.  Wave-uniform.
+struct BoundedWait {
+  unsigned long long t0, limit;
+  unsigned round;
+  bool strict;
+  __device__ __forceinline__ explicit BoundedWait(unsigned long long limit_ticks)
+      : t0(0), limit(limit_ticks), round(0), strict(limit_ticks < 100000ull) {
+    if (strict) t0 = wall_clock64();
+  }
+  // Call after a poll that did not complete; true once the limit has passed.
+  __device__ __forceinline__ bool expired() {
+    ++round;
+    if (strict) return wall_clock64() - t0 > limit;
+    if ((round & 63u) != 0u) return false;
+    const unsigned long long now = wall_clock64();
+    if (round == 64u) { t0 = now; return false; }
+    return now - t0 > limit;
+  }
+};
 
 // Writes NaN into every score this block owns: a call whose exchange failed must not leave
 // plausible numbers behind.
@@ -133,10 +158,10 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
     float mx[16], sm[16];
 #pragma unroll
     for (int q = 0; q < 16; ++q) { mx[q] = kNegBig; sm[q] = 0.f; }
-    stream_head_direct(a, qa, tok_base, Lb, g, c0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
+    stream_head_direct(a, qa, tok_base, Lb, g, c0, c1 - c0, stage, lane, [&](int st, const floatx16 &acc) {
       const int tok = c0 + st * kSub + n;
       const bool counted = (tok >= o0 && tok < o1) || (last && tok >= P && tok < Lb);
-      const bool scored = tok >= 0 && tok < P;  // a prefix token (owned or halo): its probability is formed in phase 3
+      const bool scored = tok >= 0 && tok < min(P, c1);  // a prefix token (owned or halo): its probability is formed in phase 3
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const int w = hi * 4 + (q & 3);
@@ -194,7 +219,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
       unsigned long long v[kBoxChunks];
 #pragma unroll
       for (int i = 0; i < kBoxChunks; ++i) v[i] = kEmpty64;
-      const unsigned long long t0 = wall_clock64();
+      BoundedWait wait(f.timeout_ticks);
       while (true) {
         bool missing = false;
 #pragma unroll
@@ -204,8 +229,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
         for (int i = 0; i < kBoxChunks; ++i)
           if (i < n_it && i * 64 + lane < nb && v[i] == kEmpty64) missing = true;
         if (!__any(missing)) break;
-        if (wall_clock64() - t0 > f.timeout_ticks) { wave_ok = false; break; }
-        __builtin_amdgcn_s_sleep(1);
+        if (wait.expired()) { wave_ok = false; break; }
       }
       if (!wave_ok) break;
       float m = kNegBig, s = 0.f;
@@ -248,12 +272,11 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
   if (has_group && wave_ok) {
     float *box = f.lse + (size_t)blockIdx.x * kLseRowsPerBlock + g * kRowsPerGroup + (lane & 31);
     unsigned bits = kEmpty32;
-    const unsigned long long t0 = wall_clock64();
+    BoundedWait wait(f.timeout_ticks);
     while (true) {
       if (lane < 32 && bits == kEmpty32) bits = box_peek(box);
       if (!__any(lane < 32 && bits == kEmpty32)) break;
-      if (wall_clock64() - t0 > f.timeout_ticks) { wave_ok = false; break; }
-      __builtin_amdgcn_s_sleep(1);
+      if (wait.expired()) { wave_ok = false; break; }
     }
     if (wave_ok && lane < 32) {
       box_clear(box);
@@ -275,7 +298,7 @@ __global__ __launch_bounds__(kThreads) void k_score_fused(ScoreArgs a, FusedArgs
     for (int st = 0; st < kFusedSub; ++st) {
       if (st < n_sub) {
         const int tok = c0 + st * kSub + n;
-        const bool inb = tok >= 0 && tok < P;  // only prefix tokens are scored
+        const bool inb = tok >= 0 && tok < min(P, c1);  // only prefix tokens are scored; slots past c1 were never loaded
 #pragma unroll
         for (int hl = 0; hl < 4; ++hl) {
           float sum = 0.f;

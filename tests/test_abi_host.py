@@ -188,3 +188,42 @@ def test_plan_layer_follows_algorithm_1(lib):
     assert lib.fkv_plan_layer(0, 32, 15, 100, 0.0, 0.1, 8, ctypes.byref(p)) == fk.FKV_EINVAL
     assert lib.fkv_plan_layer(0, 32, 15, 4, 0.2, 0.1, 8, ctypes.byref(p)) == fk.FKV_EINVAL
     assert lib.fkv_plan_layer(0, 32, 15, 100, 0.2, 0.1, 8, None) == fk.FKV_ENULL
+
+
+def test_score_plan_covers_every_prefix_token():
+    """Host logic of the single-pass kernel's block layout: every prefix token is owned by exactly one
+    block, no block is empty, no block computes more than its sub-tiles hold, the block budget is kept,
+    and a smaller budget never gives a smaller share."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    cases = [([32768], 8, 7, 256), ([6554], 8, 7, 256), ([2048], 8, 7, 256), ([9], 8, 7, 256), ([8], 8, 7, 256),
+             ([61440], 8, 7, 256), ([70000], 8, 7, 256), ([300, 1000, 57, 8, 2049, 131], 8, 7, 256), ([40], 8, 31, 4)]
+    for _ in range(300):
+        B = int(rng.integers(1, 9))
+        W = int(rng.integers(1, 9))
+        cases.append(([int(rng.integers(W, 9000)) for _ in range(B)], W, int(rng.integers(0, 16)) * 2 + 1,
+                      int(rng.choice([1, 7, 64, 213, 256]))))
+    for lengths, W, pk, max_blocks in cases:
+        shape = fk.make_shape(lengths, window=W, pool_kernel=pk)
+        plan = fk.fkv_score_plan(shape, max_blocks)
+        r = pk // 2
+        total_prefix = sum(L - W for L in lengths)
+        if plan is None:
+            # only when even 8 sub-tiles per block are not enough for the block budget (or nothing is to be scored)
+            cap = 256 - 2 * r
+            assert total_prefix == 0 or cap <= max(0, W - r) or \
+                sum(-(-(L - W) // cap) for L in lengths if L > W) >= max_blocks, (lengths, W, pk, max_blocks)
+            continue
+        first, own, n_sub = plan
+        assert first[0] == 0 and first[-1] <= max_blocks and 1 <= n_sub <= 8
+        for b, L in enumerate(lengths):
+            P, nb = L - W, first[b + 1] - first[b]
+            assert nb == (0 if P <= 0 else -(-P // own[b])), (lengths, W, pk, max_blocks, plan)
+            for i in range(nb):
+                o0, o1 = i * own[b], min(P, (i + 1) * own[b])
+                assert o1 > o0
+                c1 = max(L, o1 + r) if i == nb - 1 else o1 + r
+                assert c1 - (o0 - r) <= n_sub * 32, (lengths, W, pk, max_blocks, plan, i)
+    # config 2: 5 full sub-tiles per block on 213 blocks; the 6554 propagated tokens: 2 sub-tiles on 113 blocks
+    assert fk.fkv_score_plan(fk.make_shape(32768), 256) == ([0, 213], [154], 5)
+    assert fk.fkv_score_plan(fk.make_shape(6554), 256) == ([0, 113], [58], 2)

@@ -106,8 +106,11 @@ def test_window_output_rejects_bad_arguments(ctx):
         ctx.fkv_window_output(shape, q, k, k, out=torch.zeros((8 * 32 * 128 + 1,), dtype=torch.float32, device="cuda")[1:])
     assert e.value.status == fk.FKV_EALIGN
     big = fk.make_shape(50000)
-    with pytest.raises(fk.FkvError) as e:
+    with pytest.raises(ValueError):           # the binding stops a tensor shorter than the descriptor says
         ctx.fkv_window_output(big, q, k, k)
+    kbig = torch.zeros((50000, 8, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fk.FkvError) as e:
+        ctx.fkv_window_output(big, q, kbig, kbig)
     assert e.value.status == fk.FKV_EWORKSPACE
 
 
