@@ -141,6 +141,21 @@ int fkv_gather_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *k, const voi
                   const int32_t *idx_kv, const int32_t *budget_per_seq, void *k_out, void *v_out,
                   void *stream);
 
+/* fkv_score_window for callers that cannot allocate device memory or create a context: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus
+ * the context), same outputs, computed by the two-pass score kernels; the scratch they need (the
+ * per-block row statistics and the per-row normalisers) lives in a 4.3 MB array in the library's
+ * device image instead of a context's workspace, so the call allocates nothing, frees nothing and
+ * calls nothing that does.  Limits: at most 131072 tokens in at most 16 sequences per call, else
+ * FKV_EWORKSPACE; devices 0..15.  Runs on the calling thread's current device, on `stream`.  All
+ * calls on one GPU share that GPU's copy of the array: calls that overlap on one GPU (different
+ * streams without an ordering between them) race; calls ordered on one stream, or by events, are
+ * fine.  Nothing in the array has to be cleared between calls (every word a call reads, it has
+ * written before).  The first call on a device looks up the array's device address (no
+ * allocation); make that first call outside graph capture. */
+int fkv_score_window_static(const fkv_shape *shape, const void *q_win, const void *k, float *scores_group,
+                            float *scores_tsp, void *stream);
+
 /* Per-head variant of the score (Eq. 1 alone, no averaging over heads): scores_head [Hq][sum P]
  * holds the pooled saliency S^{l,h} of every query head.  With fkv_select_topk (n_rows = Hq) and
  * fkv_gather_kv_per_head it gives head-wise KV retention, the layout Sec. 5.3 contrasts with the

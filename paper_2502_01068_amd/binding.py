@@ -24,7 +24,7 @@ EXPORTS = [
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
     "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error", "fkv_compress_kv_paged", "fkv_probe_logits", "fkv_window_output",
-    "fkv_score_plan",
+    "fkv_score_window_static", "fkv_score_plan",
 ]
 
 
@@ -73,6 +73,7 @@ def load():
     lib.fkv_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i32]
     lib.fkv_destroy.argtypes = [vp]
     lib.fkv_score_window.argtypes = [vp, shp, vp, vp, vp, vp, vp]
+    lib.fkv_score_window_static.argtypes = [shp, vp, vp, vp, vp, vp]
     lib.fkv_score_plan.argtypes = [shp, i32, pi32, pi32, pi32]
     lib.fkv_select_topk.argtypes = [vp, shp, vp, i32, pi32, vp, vp]
     lib.fkv_gather_rows.argtypes = [vp, shp, vp, sz, vp, pi32, vp, vp]
@@ -213,6 +214,27 @@ def _counts(shape, counts):
     if len(counts) != shape.n_seq:
         raise ValueError("need one count per sequence")
     return counts, _i32_array(counts)
+
+
+def fkv_score_window_static(shape, q_win, k, scores_group=None, scores_tsp=None, want_tsp=True):
+    """The score call that needs no context and allocates nothing in the library (at most 131072 tokens in
+    16 sequences) -> (scores_group [Hkv, sum P] fp32, scores_tsp [sum P] fp32 or None).  Runs on the
+    tensors' device, which must be the current one."""
+    n = _Sizes(shape)
+    dev = k.device
+    if dev.index != torch.cuda.current_device():
+        raise ValueError("k is on cuda:%s, the current device is cuda:%d" % (dev.index, torch.cuda.current_device()))
+    if scores_group is None:
+        scores_group = torch.empty((shape.n_kv_heads, n.sum_p), dtype=torch.float32, device=dev)
+    if scores_tsp is None and want_tsp:
+        scores_tsp = torch.empty((n.sum_p,), dtype=torch.float32, device=dev)
+    _check(load().fkv_score_window_static(
+        ctypes.byref(shape), _dev_ptr(q_win, "q_win", _BF16, numel=n.q_win, device=dev.index),
+        _dev_ptr(k, "k", _BF16, numel=n.kv, device=dev.index),
+        _dev_ptr(scores_group, "scores_group", (torch.float32,), numel=shape.n_kv_heads * n.sum_p, device=dev.index),
+        _dev_ptr(scores_tsp, "scores_tsp", (torch.float32,), True, numel=n.sum_p, device=dev.index), _stream()),
+        "fkv_score_window_static")
+    return scores_group, scores_tsp
 
 
 class Context:

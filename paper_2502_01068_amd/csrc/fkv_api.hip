@@ -1035,6 +1035,79 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
   return enqueue_gather(ctx, g, r, st);
 }
 
+}  // extern "C"
+
+// ---- the entry point that allocates nothing -------------------------------------------------
+// Scratch of fkv_score_window_static: the two-pass score kernels' per-block row statistics and
+// the per-row normalisers, for up to kStaticMaxTokens tokens in up to kStaticMaxSeqs sequences.
+// Every GPU the library runs on holds its own copy of the array until the process ends.
+namespace {
+constexpr int64_t kStaticMaxTokens = 131072;
+constexpr int kStaticMaxSeqs = 16;
+constexpr int kStaticStatBlocks = (int)(kStaticMaxTokens / kStatsChunk) + kStaticMaxSeqs;
+constexpr size_t kStaticPartialBytes = (size_t)kStaticStatBlocks * kMaxVGroups * kRowsPerGroup * sizeof(float2);
+constexpr size_t kStaticRowstatBytes = (size_t)kStaticMaxSeqs * kMaxVGroups * kRowsPerGroup * sizeof(float);
+constexpr size_t kStaticScratchBytes = kStaticPartialBytes + kStaticRowstatBytes;  // 4.3 MB
+static_assert(kStaticPartialBytes % 256 == 0, "rowstat stays aligned");
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+// `scratch` above is a host-side stand-in in host code, not an address a kernel can use: the device
+// address is looked up once per device and kept here.
+struct StaticDevice {
+  unsigned char *ptr = nullptr;
+  int n_cu = 0;
+};
+StaticDevice g_static[16];
+std::mutex g_static_mu;
+
+int static_device(StaticDevice *out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= 16) return FKV_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  StaticDevice &d = g_static[dev];
+  if (d.ptr == nullptr) {
+    unsigned char *p = nullptr;
+    e = hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (p == nullptr) return FKV_EHIP;
+    int n_cu = 0;
+    e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return hip_fail(e);
+    d.n_cu = n_cu;
+    d.ptr = p;
+  }
+  *out = d;
+  return FKV_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int fkv_score_window_static(const fkv_shape *shape, const void *q_win, const void *k, float *scores_group,
+                            float *scores_tsp, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!q_win || !k || (!scores_group && r.sum_p > 0)) return FKV_ENULL;
+  if (misaligned(q_win) || misaligned(k) || misaligned(scores_group) || misaligned(scores_tsp)) return FKV_EALIGN;
+  if (r.total > kStaticMaxTokens || r.n_seq > kStaticMaxSeqs) return FKV_EWORKSPACE;
+  StaticDevice d;
+  rc = static_device(&d);
+  if (rc != FKV_OK) return rc;
+  ScoreWs w{};
+  w.partial = reinterpret_cast<float2 *>(d.ptr);
+  w.partial_stride = kStaticStatBlocks;
+  w.rowstat = reinterpret_cast<float *>(d.ptr + kStaticPartialBytes);
+  w.n_cu = d.n_cu;
+  w.score_path = 1;  // the two-pass kernels: no resident-grid requirement, nothing to reset between calls
+  return enqueue_score(w, shape, r, q_win, k, scores_group, scores_tsp, nullptr, static_cast<hipStream_t>(stream));
+}
+
 int fkv_set_score_path(fkv_ctx *ctx, int mode) {
   if (!ctx) return FKV_ENULL;
   if (mode < 0 || mode > 2) return FKV_EINVAL;
