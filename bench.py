@@ -372,6 +372,32 @@ def run_window_output(args):
     e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / args.steps
+
+    # the same output together with the scores: one call (V once, K twice, no grid exchange) against the two calls
+    sg = torch.empty((8, L - 8), dtype=torch.float32, device="cuda")
+    st = torch.empty((L - 8,), dtype=torch.float32, device="cuda")
+
+    def timed(fn):
+        for i in range(args.warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / args.steps
+
+    fused_us = timed(lambda i: ctx.fkv_score_window_output(shape, q, kv[i % 4][0], kv[i % 4][1], sg, st, out))
+    sg1 = sg.clone()
+
+    def two_calls(i):
+        ctx.fkv_score_window(shape, q, kv[i % 4][0], sg, st)
+        ctx.fkv_window_output(shape, q, kv[i % 4][0], kv[i % 4][1], out=out)
+
+    pair_us = timed(two_calls)
+    torch.cuda.synchronize()
+    assert torch.allclose(sg, sg1, rtol=1e-3, atol=1e-37), "the fused call and fkv_score_window disagree"
     # parity of the timed configuration on sampled rows: library matrix products in fp64 on the GPU's inputs
     k, v = (t.double() for t in kv[(args.steps - 1) % 4])
     worst = 0.0
@@ -393,6 +419,10 @@ def run_window_output(args):
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None},
         "path": {"algorithmic_bytes": nbytes, "TFLOPs": flops / (us * 1e-6) / 1e12,
                  "sampled_parity_worst_row_error": worst,
+                 "scores_and_output": {"fkv_score_window_output_us": fused_us,
+                                       "fkv_score_window_then_fkv_window_output_us": pair_us,
+                                       "algorithmic_bytes": nbytes + 4 * 9 * (L - 8),
+                                       "frac_of_peak": (nbytes + 4 * 9 * (L - 8)) / (fused_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
                  "timing": "HIP events around back-to-back calls (two launches each)"}}))
     assert ctx.fkv_query_error() == 0
     ctx.close()

@@ -212,6 +212,16 @@ int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, co
 int fkv_window_output(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, const void *v,
                       float *out, void *stream);
 
+/* Scores and the window rows' attention output from one set of probabilities: what fkv_score_window
+ * and fkv_window_output compute (Sec. 4.2 Eq. 1-2, App. B.1; Sec. 5.1: the layer's fused attention
+ * kernel does not expose Att, so the estimation step recomputes it), in one call that reads V once and
+ * K twice and needs no grid-wide exchange: the pass that forms the output also leaves every softmax
+ * row's normaliser, and a second pass over K (largely served by the caches the first one filled)
+ * turns logits into pooled, head-averaged scores.  Arguments and outputs as in the two calls;
+ * scores_tsp may be NULL. */
+int fkv_score_window_output(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, const void *v,
+                            float *scores_group, float *scores_tsp, float *out, void *stream);
+
 /* Paged cache layout (the serving layout the paper's Limitations section says the method has to
  * fit): a pool of pages [n_pages][page_size][Hkv][d] bf16 per tensor and a DEVICE block table
  * [B][max_pages_per_seq] int32; logical token t of sequence b lives in page

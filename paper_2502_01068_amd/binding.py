@@ -24,7 +24,7 @@ EXPORTS = [
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
     "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error", "fkv_compress_kv_paged", "fkv_probe_logits", "fkv_window_output",
-    "fkv_score_window_static", "fkv_score_plan",
+    "fkv_score_window_static", "fkv_score_plan", "fkv_score_window_output",
 ]
 
 
@@ -83,6 +83,7 @@ def load():
     lib.fkv_gather_kv_per_head.argtypes = [vp, shp, vp, vp, vp, pi32, vp, vp, vp]
     lib.fkv_decode_attention.argtypes = [vp, shp, vp, vp, vp, i32, pi32, vp, vp]
     lib.fkv_window_output.argtypes = [vp, shp, vp, vp, vp, vp, vp]
+    lib.fkv_score_window_output.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, vp]
     lib.fkv_gather_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp]
     lib.fkv_compress_kv_paged.argtypes = [vp, shp, vp, vp, vp, pi32, vp, i32, i32, i64, vp, vp, vp, vp]
     lib.fkv_decode_attention_paged.argtypes = [vp, shp, vp, vp, vp, vp, i32, i32, i64, pi32, vp, vp]
@@ -417,6 +418,24 @@ class Context:
                                         self._p(k, "k", _BF16, numel=n.kv), self._p(v, "v", _BF16, numel=n.kv),
                                         self._p(out, "out", (torch.float32,), numel=n.q_win), _stream()), "fkv_window_output")
         return out
+
+    def fkv_score_window_output(self, shape, q_win, k, v, scores_group=None, scores_tsp=None, out=None, want_tsp=True):
+        """Scores and the window rows' attention output in one call (V read once, K twice, no grid exchange)
+        -> (scores_group [Hkv, sum P], scores_tsp [sum P] or None, out [B,W,Hq,d] fp32)"""
+        n = _Sizes(shape)
+        dev = k.device
+        if scores_group is None:
+            scores_group = torch.empty((shape.n_kv_heads, n.sum_p), dtype=torch.float32, device=dev)
+        if scores_tsp is None and want_tsp:
+            scores_tsp = torch.empty((n.sum_p,), dtype=torch.float32, device=dev)
+        if out is None:
+            out = torch.empty((shape.n_seq, shape.window, shape.n_q_heads, shape.head_dim), dtype=torch.float32, device=dev)
+        _check(load().fkv_score_window_output(
+            self.handle, ctypes.byref(shape), self._p(q_win, "q_win", _BF16, numel=n.q_win), self._p(k, "k", _BF16, numel=n.kv),
+            self._p(v, "v", _BF16, numel=n.kv), self._p(scores_group, "scores_group", (torch.float32,), numel=shape.n_kv_heads * n.sum_p),
+            self._p(scores_tsp, "scores_tsp", (torch.float32,), True, numel=n.sum_p),
+            self._p(out, "out", (torch.float32,), numel=n.q_win), _stream()), "fkv_score_window_output")
+        return scores_group, scores_tsp, out
 
     def _paging(self, shape, block_table, k_pages, v_pages, v_required):
         if block_table.dim() != 2 or block_table.shape[0] != shape.n_seq:

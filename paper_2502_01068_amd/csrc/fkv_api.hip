@@ -278,9 +278,37 @@ ScoreWs ws_of(fkv_ctx *ctx) {
   return w;
 }
 
-int enqueue_score(const ScoreWs &w, const fkv_shape *sh, const Resolved &r, const void *q_win, const void *k,
-                  float *scores_group, float *scores_tsp, float *scores_head, hipStream_t st) {
-  ScoreArgs a{};
+// Second pass of the two-pass score kernels: probabilities from the per-row normalisers in
+// a.rowstat, window sum, pooling, head means.  Tiles overlap by the pooling halo.
+int enqueue_scores_pass2(const ScoreWs &w, ScoreArgs &a, const Resolved &r, hipStream_t st) {
+  const int n_cu = w.n_cu > 0 ? w.n_cu : 256;
+  {
+    int sub = scores_sub_short();
+    const int64_t per_cu = (r.sum_p + n_cu - 1) / n_cu + 2 * a.pool_r;
+    if (per_cu > (int64_t)sub * 32) sub = (int)((per_cu + 31) / 32);
+    const int sub_max = r.V > kMaxKvHeads ? scores_sub_wide() : scores_sub_long();
+    if (sub > sub_max) sub = sub_max;
+    while (sub * 32 - 2 * a.pool_r < 1) ++sub;
+    a.tile_sub = sub;
+  }
+  const int tout = a.tile_sub * 32 - 2 * a.pool_r;
+  int nb = 0;
+  for (int b = 0; b < r.n_seq; ++b) {
+    a.map.blk[b] = nb;
+    const int P = r.cu[b + 1] - r.cu[b] - r.W;
+    nb += (P + tout - 1) / tout;
+  }
+  a.map.blk[r.n_seq] = nb;
+  if (nb > 0) {
+    Timed t(w.prof, st, KID_SCORES);
+    const hipError_t e = launch_scores(a, nb, st);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return FKV_OK;
+}
+
+void fill_score_args(ScoreArgs &a, const ScoreWs &w, const fkv_shape *sh, const Resolved &r, const void *q_win,
+                     const void *k, float *scores_group, float *scores_tsp, float *scores_head) {
   a.q_win = static_cast<const uint16_t *>(q_win);
   a.k = static_cast<const uint16_t *>(k);
   a.partial = w.partial;
@@ -298,6 +326,12 @@ int enqueue_score(const ScoreWs &w, const fkv_shape *sh, const Resolved &r, cons
   a.pool_mode = sh->pool_mode;
   a.sum_p = r.sum_p;
   fill_map(r, &a.map);
+}
+
+int enqueue_score(const ScoreWs &w, const fkv_shape *sh, const Resolved &r, const void *q_win, const void *k,
+                  float *scores_group, float *scores_tsp, float *scores_head, hipStream_t st) {
+  ScoreArgs a{};
+  fill_score_args(a, w, sh, r, q_win, k, scores_group, scores_tsp, scores_head);
 
   // Single pass over K when every block of the batch can be resident at once.
   if (w.fused_part != nullptr) {
@@ -358,30 +392,7 @@ int enqueue_score(const ScoreWs &w, const fkv_shape *sh, const Resolved &r, cons
   { Timed t(w.prof, st, KID_COMBINE); e = launch_combine(a, st); }
   if (e != hipSuccess) return hip_fail(e);
 
-  // pass 2: scores of the prefix tokens; tiles overlap by the pooling halo
-  {
-    int sub = scores_sub_short();
-    const int64_t per_cu = (r.sum_p + n_cu - 1) / n_cu + 2 * a.pool_r;
-    if (per_cu > (int64_t)sub * 32) sub = (int)((per_cu + 31) / 32);
-    const int sub_max = r.V > kMaxKvHeads ? scores_sub_wide() : scores_sub_long();
-    if (sub > sub_max) sub = sub_max;
-    while (sub * 32 - 2 * a.pool_r < 1) ++sub;
-    a.tile_sub = sub;
-  }
-  const int tout = a.tile_sub * 32 - 2 * a.pool_r;
-  nb = 0;
-  for (int b = 0; b < r.n_seq; ++b) {
-    a.map.blk[b] = nb;
-    const int P = r.cu[b + 1] - r.cu[b] - r.W;
-    nb += (P + tout - 1) / tout;
-  }
-  a.map.blk[r.n_seq] = nb;
-  if (nb > 0) {
-    Timed t(w.prof, st, KID_SCORES);
-    e = launch_scores(a, nb, st);
-    if (e != hipSuccess) return hip_fail(e);
-  }
-  return FKV_OK;
+  return enqueue_scores_pass2(w, a, r, st);
 }
 
 void fill_rowset(SelectRowSet *rs, const float *scores, int64_t stride, int n_rows, int32_t *out,
@@ -785,16 +796,11 @@ int decode_common(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const voi
 }
 }  // namespace
 
-int fkv_window_output(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, const void *v,
-                      float *out, void *stream) {
-  Resolved r;
-  int rc = resolve(shape, &r);
-  if (rc != FKV_OK) return rc;
-  if (!q_win || !k || !v || !out) return FKV_ENULL;
-  if (misaligned(q_win) || misaligned(k) || misaligned(v) || misaligned(out)) return FKV_EALIGN;
-  rc = check_ctx(ctx, r);
-  if (rc != FKV_OK) return rc;
-  ctx->ev_prev = nullptr;
+namespace {
+// Launches the window rows' attention output; rowstat != nullptr also stores every softmax row's
+// log-sum-exp there and keeps K in the caches for the score pass that follows.
+int enqueue_wout(fkv_ctx *ctx, const fkv_shape *shape, const Resolved &r, const void *q_win, const void *k, const void *v,
+                 float *out, float *rowstat, hipStream_t st) {
   WoutArgs a{};
   a.q_win = static_cast<const uint16_t *>(q_win);
   a.k = static_cast<const uint16_t *>(k);
@@ -802,6 +808,8 @@ int fkv_window_output(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, c
   a.part_o = reinterpret_cast<float *>(ctx->ws + ctx->lay.wout_o);
   a.part_ms = reinterpret_cast<float2 *>(ctx->ws + ctx->lay.wout_ms);
   a.out = out;
+  a.rowstat = rowstat;
+  a.keep_k = rowstat != nullptr;
   int tiles_max = 1;
   for (int b = 0; b <= r.n_seq; ++b) a.cu[b] = r.cu[b];
   for (int b = 0; b < r.n_seq; ++b) tiles_max = std::max(tiles_max, (r.cu[b + 1] - r.cu[b] + 31) / 32);
@@ -814,10 +822,45 @@ int fkv_window_output(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, c
   a.causal = shape->causal;
   const float scale = shape->softmax_scale > 0.f ? shape->softmax_scale : 1.0f / sqrtf((float)shape->head_dim);
   a.scale_log2e = scale * 1.4426950408889634f;
-  hipStream_t st = static_cast<hipStream_t>(stream);
   Timed t(ctx, st, KID_WOUT);
   const hipError_t e = launch_wout(a, st);
   return e == hipSuccess ? FKV_OK : hip_fail(e);
+}
+}  // namespace
+
+int fkv_window_output(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, const void *v,
+                      float *out, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!q_win || !k || !v || !out) return FKV_ENULL;
+  if (misaligned(q_win) || misaligned(k) || misaligned(v) || misaligned(out)) return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  return enqueue_wout(ctx, shape, r, q_win, k, v, out, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int fkv_score_window_output(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, const void *k, const void *v,
+                            float *scores_group, float *scores_tsp, float *out, void *stream) {
+  Resolved r;
+  int rc = resolve(shape, &r);
+  if (rc != FKV_OK) return rc;
+  if (!q_win || !k || !v || !out || (!scores_group && r.sum_p > 0)) return FKV_ENULL;
+  if (misaligned(q_win) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(scores_group) ||
+      misaligned(scores_tsp))
+    return FKV_EALIGN;
+  rc = check_ctx(ctx, r);
+  if (rc != FKV_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const ScoreWs w = ws_of(ctx);
+  // one pass over K and V: the window rows' output and, as a by-product, every softmax row's normaliser
+  rc = enqueue_wout(ctx, shape, r, q_win, k, v, out, w.rowstat, st);
+  if (rc != FKV_OK || r.sum_p == 0) return rc;
+  // second pass over K (what the first pass left in the caches is reused): the scores
+  ScoreArgs a{};
+  fill_score_args(a, w, shape, r, q_win, k, scores_group, scores_tsp, nullptr);
+  a.k_cached = r.V <= kMaxKvHeads ? 1 : 0;
+  return enqueue_scores_pass2(w, a, r, st);
 }
 
 int fkv_decode_attention(fkv_ctx *ctx, const fkv_shape *shape, const void *q, const void *k, const void *v,

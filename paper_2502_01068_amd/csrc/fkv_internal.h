@@ -86,6 +86,7 @@ struct ScoreArgs {
   int pool_mode;          // FKV_POOL_AVG / FKV_POOL_MAX
   int chunk;              // tokens per block in the stats launch (multiple of 32)
   int tile_sub;           // 32-token sub-tiles per block in the scores launch
+  int k_cached;           // scores launch: K was streamed by the launch just before (read it with plain loads)
   int64_t sum_p;          // row stride of scores_group
 };
 
@@ -191,6 +192,9 @@ struct WoutArgs {
   int n_split;            // blocks per (sequence, virtual group)
   int causal;
   float scale_log2e;
+  float *rowstat;         // [n_seq][V*32] or nullptr: receives each softmax row's log-sum-exp (log2 units), the
+                          // normaliser the second pass of the two-pass score kernels reads
+  int keep_k;             // K is read with plain loads (it will be read again soon) instead of non-temporal ones
 };
 int wout_tiles_per_block_min(void);
 hipError_t launch_wout(const WoutArgs &a, hipStream_t s);

@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void k_combine(ScoreArgs a) {
 // kMaxSub 32-token sub-tiles per block at most; a.tile_sub of them are used (host-chosen so that
 // the launch is about one block per CU).  The window sums go straight into their own LDS array,
 // next to the waves' staging tiles.
-template <int kMaxSub, int kGroups>
+template <int kMaxSub, int kGroups, bool kStreaming = true>
 __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
   constexpr int kSlots = kMaxSub * kSub;
   __shared__ __attribute__((aligned(16))) uint8_t stage_all[kWaves * kStageBytes];
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void k_scores(ScoreArgs a) {
 #pragma unroll
     for (int q = 0; q < 16; ++q) cst[q] = rs[(q >> 2) * 8 + hi * 4 + (q & 3)];
 
-    stream_head<true>(a, qa, tok_base, Lb, g, j0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
+    stream_head<kStreaming>(a, qa, tok_base, Lb, g, j0, n_sub, stage, lane, [&](int st, const floatx16 &acc) {
       const int tok = j0 + st * kSub + n;
       const bool inb = tok >= 0 && tok < P;  // only prefix tokens are scored
 #pragma unroll
@@ -169,10 +169,12 @@ hipError_t launch_combine(const ScoreArgs &a, hipStream_t s) {
 hipError_t launch_scores(const ScoreArgs &a, int n_blocks, hipStream_t s) {
   if (a.V > kMaxKvHeads)  // twice the heads in LDS: half the tile
     hipLaunchKernelGGL((k_scores<kScoresSubWide, kMaxVGroups>), dim3(n_blocks), dim3(kThreads), 0, s, a);
-  else if (a.tile_sub <= kScoresSubShort)
+  else if (a.tile_sub <= kScoresSubShort && !a.k_cached)
     hipLaunchKernelGGL((k_scores<kScoresSubShort, kMaxKvHeads>), dim3(n_blocks), dim3(kThreads), 0, s, a);
-  else
+  else if (!a.k_cached)
     hipLaunchKernelGGL((k_scores<kScoresSubLong, kMaxKvHeads>), dim3(n_blocks), dim3(kThreads), 0, s, a);
+  else  // K was just read by the launch before: plain loads, so that what the caches still hold is used
+    hipLaunchKernelGGL((k_scores<kScoresSubLong, kMaxKvHeads, false>), dim3(n_blocks), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 

@@ -39,6 +39,7 @@ __device__ __forceinline__ float max_across_halves(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+template <bool kKeepK>
 __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
   __shared__ __attribute__((aligned(16))) uint8_t lds_all[kWoWaves * kWoTileBytes];
   __shared__ float2 ms_lds[kWoWaves][kRowsPerGroup];
@@ -65,7 +66,7 @@ __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
   // direct-to-LDS tile loads: lane l of load i lands at tile offset i*1024 + 16 l, i.e. token slot
   // 4 i + l/16, 16-byte column l%16.  The K tile is XOR-swizzled (from the global side), V is plain.
   // Both streams are read once: the loads are marked non-temporal (measured 34.3 instead of 38.6 us per call at
-  // 32768 tokens).
+  // 32768 tokens), except K when the caller reads it again right after this launch (kKeepK).
   const int c = lane & 15, tq = lane >> 4;
   const size_t tok_stride = (size_t)a.Hkv * kHeadDim;
   const uint16_t *kbase = a.k + (size_t)vg_kv_head(a, g) * kHeadDim;
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(kWoThreads) void k_wout_partial(WoutArgs a) {
       const int slot = i * 4 + tq;
       const int t = min(tile * kSub + slot, Lb - 1);
       const uint16_t *src = kbase + (size_t)(tok_base + t) * tok_stride + ((c ^ (slot & 15)) << 3);
-      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(ktile + i * 1024), 16, 0, 2);
+      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(ktile + i * 1024), 16, 0, kKeepK ? 0 : 2);
     }
   };
   auto issue_v = [&](int tile) {
@@ -242,7 +243,11 @@ __global__ __launch_bounds__(256) void k_wout_merge(WoutArgs a) {
   const int idx = blockIdx.y * kWoMergeOutputs + (threadIdx.x >> 2);
   const int row = idx >> 5, chunk = idx & 31;
   const int hl = row >> 3, w = row & 7;
-  if (hl >= vg_heads(a, g) || w >= a.W) return;  // the four lanes of an output leave together
+  const bool first = j == 0 && chunk == 0;        // the lane that reports the row's normaliser
+  if (hl >= vg_heads(a, g) || w >= a.W) {         // the four lanes of an output leave together
+    if (first && a.rowstat) a.rowstat[(size_t)bg * kRowsPerGroup + row] = 0.f;
+    return;
+  }
   const float2 *ms = a.part_ms + (size_t)bg * a.n_split * kRowsPerGroup + row;
   const float *po = a.part_o + (size_t)bg * a.n_split * kWoRowFloats + row * kHeadDim + chunk * 4;
   constexpr int kBatch = 8;
@@ -282,13 +287,17 @@ __global__ __launch_bounds__(256) void k_wout_merge(WoutArgs a) {
     num.z += __shfl_xor(num.z, d); num.w += __shfl_xor(num.w, d);
   }
   if (j != 0) return;
+  if (first && a.rowstat) a.rowstat[(size_t)bg * kRowsPerGroup + row] = M + __log2f(den);
   const float inv = 1.f / den;
   float *dst = a.out + (((size_t)b * a.W + w) * a.Hq + vg_head0(a, g) + hl) * kHeadDim + chunk * 4;
   *reinterpret_cast<float4 *>(dst) = make_float4(num.x * inv, num.y * inv, num.z * inv, num.w * inv);
 }
 
 hipError_t launch_wout(const WoutArgs &a, hipStream_t s) {
-  hipLaunchKernelGGL(k_wout_partial, dim3(a.n_split, a.V, a.n_seq), dim3(kWoThreads), 0, s, a);
+  if (a.keep_k)
+    hipLaunchKernelGGL(k_wout_partial<true>, dim3(a.n_split, a.V, a.n_seq), dim3(kWoThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(k_wout_partial<false>, dim3(a.n_split, a.V, a.n_seq), dim3(kWoThreads), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_wout_merge, dim3(a.n_seq * a.V, kWoRowFloats / 4 / kWoMergeOutputs), dim3(256), 0, s, a);

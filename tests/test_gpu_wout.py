@@ -153,3 +153,66 @@ def test_window_output_many_sequences_and_many_splits():
     print("  worst %.2e" % _run(c, [70000], 4, 1, seed=76), flush=True)
     print("  worst %.2e" % _run(c, [70001], 2, 2, W=3, seed=77), flush=True)
     c.close()
+
+
+# ---- scores and window output in one call (fkv_score_window_output) ----------------------------------
+
+@pytest.mark.parametrize("lens,Hq,Hkv,W,pk,pool_mode,scale,causal", [
+    ([2048], 32, 8, 8, 7, "avg", 0.0, True),
+    ([2048], 32, 8, 8, 7, "max", 0.0, True),
+    ([9], 32, 8, 8, 7, "max", 0.0, True),
+    ([8], 32, 8, 8, 7, "max", 0.0, True),              # no prefix token: only the output exists
+    ([300, 8, 2049, 64, 4097, 33], 32, 8, 8, 7, "avg", 0.0, True),
+    ([1333], 12, 4, 7, 9, "max", 0.05, True),
+    ([1333], 16, 2, 5, 3, "avg", 0.0, False),
+    ([900], 64, 8, 8, 7, "max", 0.0, True),            # G = 8: two row tiles per KV head
+    ([1267], 3, 3, 4, 27, "avg", 0.0, True),           # pooling radius beyond the window
+])
+def test_score_window_output_against_oracle(ctx, lens, Hq, Hkv, W, pk, pool_mode, scale, causal):
+    from parity import assert_scores_close
+    print("case: scores + window output lens=%s Hq=%d Hkv=%d W=%d pk=%d %s" % (lens, Hq, Hkv, W, pk, pool_mode), flush=True)
+    B, d, tot = len(lens), 128, sum(lens)
+    q = wl.normal_bf16(80, 0, "q_win", (B, W, Hq, d))
+    k = wl.normal_bf16(80, 0, "k", (tot, Hkv, d))
+    v = wl.normal_bf16(80, 0, "v", (tot, Hkv, d))
+    shape = fk.make_shape(lens, n_q_heads=Hq, n_kv_heads=Hkv, window=W, pool_kernel=pk, pool_mode=pool_mode,
+                          softmax_scale=scale, causal=causal)
+    dq, dk, dv = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    sg, st, out = ctx.fkv_score_window_output(shape, dq, dk, dv)
+    alone = ctx.fkv_window_output(shape, dq, dk, dv)
+    torch.cuda.synchronize()
+    assert torch.equal(out, alone)            # the same kernels formed it: bit-identical
+    sg, st, out = sg.cpu().numpy(), st.cpu().numpy(), out.cpu().numpy()
+    o = col = 0
+    for b, n in enumerate(lens):
+        P = n - W
+        ref_o = oracle.window_output(q[b], k[o:o + n], v[o:o + n], scale or None, causal, "f64")
+        _close(out[b], ref_o, "out seq %d" % b)
+        ref = oracle.score_window(q[b], k[o:o + n], pk, pool_mode, scale=(scale or None), causal=causal, precision="f64")
+        assert_scores_close(sg[:, col:col + P], ref["scores_group"], "scores_group seq %d" % b)
+        assert_scores_close(st[col:col + P], ref["scores_tsp"], "scores_tsp seq %d" % b)
+        o += n
+        col += P
+    assert ctx.fkv_query_error() == 0
+
+
+def test_score_window_output_full_size_32k():
+    """Config 2's layer: scores element by element against the oracle, output against the stand-alone call."""
+    from parity import assert_scores_close
+    print("case: scores + window output at L=32768", flush=True)
+    L = 32768
+    s = wl.make_sequence(0, L, with_x=False)
+    c = fk.Context(max_total_tokens=L, max_seqs=1)
+    try:
+        shape = fk.make_shape(L, pool_mode="avg")
+        q, k, v = dev_bf16(s["q_win"]), dev_bf16(s["k"]), dev_bf16(s["v"])
+        sg, st, out = c.fkv_score_window_output(shape, q, k, v)
+        alone = c.fkv_window_output(shape, q, k, v)
+        torch.cuda.synchronize()
+        assert torch.equal(out, alone)
+        ref = oracle.score_window(s["q_win"], s["k"], 7, "avg", precision="f32")
+        print("  scores: group %.2e tsp %.2e" % (assert_scores_close(sg.cpu().numpy(), ref["scores_group"], "scores_group"),
+                                                 assert_scores_close(st.cpu().numpy(), ref["scores_tsp"], "scores_tsp")), flush=True)
+        assert c.fkv_query_error() == 0
+    finally:
+        c.close()
