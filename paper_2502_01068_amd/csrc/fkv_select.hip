@@ -110,16 +110,24 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
     const uint32_t span = (1u << s) - 1u;  // s <= 21 here
     for (int ch = 0; ch < n_chunks; ++ch) {
       if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
+      // Valid keys lie in [0x007FFFFF, 0xFF800000] and span < 2^21, so a key below lo (or an empty
+      // slot) wraps above span: one unsigned compare per key.  A wave reserves list space for all its
+      // candidates with one LDS atomic (a scan over the lanes' counts gives each lane its place).
+      uint32_t mine = 0;
 #pragma unroll
-      for (int q = 0; q < kQ; ++q) {
-        // Valid keys lie in [0x007FFFFF, 0xFF800000] and span < 2^21, so a key below lo (or an
-        // empty slot) wraps above span: one unsigned compare per key, one branch per item.
-        const uint32_t r0 = key[4 * q] - lo, r1 = key[4 * q + 1] - lo, r2 = key[4 * q + 2] - lo, r3 = key[4 * q + 3] - lo;
-        if (min(min(r0, r1), min(r2, r3)) <= span) {
-          if (r0 <= span) cand[atomicAdd(&bcast[4], 1u)] = r0;
-          if (r1 <= span) cand[atomicAdd(&bcast[4], 1u)] = r1;
-          if (r2 <= span) cand[atomicAdd(&bcast[4], 1u)] = r2;
-          if (r3 <= span) cand[atomicAdd(&bcast[4], 1u)] = r3;
+      for (int e = 0; e < kKpt; ++e) mine += (key[e] - lo <= span) ? 1u : 0u;
+      const uint32_t inc = wave_scan_add(mine);
+      const uint32_t wave_n = wave_last(inc);
+      if (wave_n == 0) continue;
+      uint32_t wave_base = 0;
+      if (lane == 63) wave_base = atomicAdd(&bcast[4], wave_n);
+      wave_base = wave_last(wave_base);
+      if (mine != 0) {
+        uint32_t at = wave_base + inc - mine;
+#pragma unroll
+        for (int e = 0; e < kKpt; ++e) {
+          const uint32_t rel = key[e] - lo;
+          if (rel <= span) cand[at++] = rel;
         }
       }
     }

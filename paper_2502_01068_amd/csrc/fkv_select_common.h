@@ -124,31 +124,20 @@ __device__ __forceinline__ void compact_chunk(const uint32_t (&key)[kKpt], uint3
       for (int e = 0; e < 4; ++e) c += (key[4 * q + e] > T ? 1u : 0u) + (key[4 * q + e] == T ? 0x10000u : 0u);
       cnt[q] = c;
     }
-    // Kept counts per (q, lane) item, packed (low 16 bits: keys > T, high 16 bits: keys == T).
-    // Index order inside the wave is item order q*64 + lane; lane l scans items 8l .. 8l+7 from a
-    // wave-private LDS table, the 64 lanes scan their sums, and the table is overwritten with the
-    // exclusive prefix of every item.
-    uint32_t *tbl = scan_tbl + wave * (64 * kMaxKpt);  // 64*kQ table entries, then up to 64*kKpt staged outputs
+    // Kept counts per (q, lane) item, packed (low 16 bits: keys > T, high 16 bits: keys == T; a wave holds
+    // at most 2048 keys, so neither field overflows).  Index order inside the wave is item order
+    // q*64 + lane: the exclusive prefix of item (q, lane) is the total of the items of all q' < q plus
+    // an in-wave scan over the lanes of q, all on DPP lane routing (no LDS round trip).
+    uint32_t *tbl = scan_tbl + wave * (64 * kMaxKpt);  // up to 64*kKpt staged outputs of this wave
+    uint32_t pq[kQ];
+    uint32_t wave_tot = 0;
 #pragma unroll
-    for (int q = 0; q < kQ; ++q) tbl[q * 64 + lane] = cnt[q];
-    wave_sync_lds();
-    uint32_t item[kQ];
-#pragma unroll
-    for (int i = 0; i < kQ; ++i) item[i] = tbl[kQ * lane + i];
-    uint32_t mine = 0;
-#pragma unroll
-    for (int i = 0; i < kQ; ++i) mine += item[i];
-    const uint32_t inc = wave_scan_add(mine);
-    const uint32_t wave_tot = wave_last(inc);
-    uint32_t pre = inc - mine;
-    wave_sync_lds();
-#pragma unroll
-    for (int i = 0; i < kQ; ++i) {
-      tbl[kQ * lane + i] = pre;
-      pre += item[i];
+    for (int q = 0; q < kQ; ++q) {
+      const uint32_t inc = wave_scan_add(cnt[q]);
+      pq[q] = wave_tot + inc - cnt[q];
+      wave_tot += wave_last(inc);
     }
-    __syncthreads();  // wsum is free (previous readers are past their loop); tables are complete
-    if (lane == 0) wsum[wave] = wave_tot;
+    if (lane == 0) wsum[wave] = wave_tot;  // free: every caller leaves a barrier behind its last use of wsum
     __syncthreads();
     uint32_t before_w = 0, total = 0;
     for (int w = 0; w < kSelWaves; ++w) {
@@ -158,10 +147,6 @@ __device__ __forceinline__ void compact_chunk(const uint32_t (&key)[kKpt], uint3
     }
     // Kept indices are first placed in the wave's LDS region (its outputs are consecutive in the
     // result because index order is kept), then written out with full 64-lane stores.
-    uint32_t pq[kQ];
-#pragma unroll
-    for (int q = 0; q < kQ; ++q) pq[q] = tbl[q * 64 + lane];
-    wave_sync_lds();  // every lane holds its prefixes: the region can be reused for staging
     const uint32_t gt0 = run_gt + (before_w & 0xFFFFu), eq0 = run_eq + (before_w >> 16);
     const uint32_t wave_base = gt0 + min(eq0, need_eq);
     const uint32_t wave_end = gt0 + (wave_tot & 0xFFFFu) + min(eq0 + (wave_tot >> 16), need_eq);
@@ -172,6 +157,7 @@ __device__ __forceinline__ void compact_chunk(const uint32_t (&key)[kKpt], uint3
       uint32_t gt_before = gt0 + (pq[q] & 0xFFFFu);
       uint32_t eq_before = eq0 + (pq[q] >> 16);
       const int i0 = i_chunk + slot_pos<kKpt>(wave, lane, q);
+      if (cnt[q] == 0) continue;  // most items keep nothing
       if ((cnt[q] >> 16) == 0) {
         // no key of this item ties with T: branch-free placement
         int32_t *dst = stg + (gt_before + min(eq_before, need_eq) - wave_base);
