@@ -30,13 +30,14 @@ WORKLOADS = {
 def kernel_algorithmic_bytes(L, k_tsp, budget, Hq=32, Hkv=8, d=128, hidden=4096, W=8):
     """Bytes each kernel must move once (the whole-path figure counts K once, in k_stats)."""
     P = L - W
+    rows = Hkv + (1 if k_tsp else 0)   # score rows written and ranked: one per KV head, plus the all-head row of the TSP leg
     return {
         "k_stats": L * Hkv * d * 2 + W * Hq * d * 2,
         "k_combine": 0,
-        "k_scores": 4 * (Hkv + 1) * P,                       # the scores it writes; its K re-read is overhead
-        "k_select": 4 * (Hkv + 1) * P + 4 * (k_tsp + Hkv * budget),
+        "k_scores": 4 * rows * P,                            # the scores it writes; its K re-read is overhead
+        "k_select": 4 * rows * P + 4 * (k_tsp + Hkv * budget),
         "k_gather": 2 * k_tsp * hidden * 2 + 2 * 2 * Hkv * budget * d * 2 + 4 * (k_tsp + Hkv * budget),
-        "k_score_fused": L * Hkv * d * 2 + W * Hq * d * 2 + 4 * (Hkv + 1) * P,   # K once + the scores it writes
+        "k_score_fused": L * Hkv * d * 2 + W * Hq * d * 2 + 4 * rows * P,   # K once + the scores it writes
     }
 
 
@@ -434,6 +435,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="config2_L32768", choices=sorted(WORKLOADS) + ["config4_ragged", "config5_chain", "decode", "logits_probe", "window_output"])
+    ap.add_argument("--length", type=int, default=0, help="single-sequence workloads: override the context length "
+                    "(k_tsp = round-half-up(0.2 L), kv budget = min(2048, L)); e.g. 6554 is a layer after the TSP layer")
+    ap.add_argument("--no-tsp", action="store_true", help="single-sequence workloads: KVCompress only (no TSP leg, no hidden rows)")
     ap.add_argument("--budget", type=int, default=0, help="config4_ragged: KV budget per KV head (default: sweep 512, 1024, 2048)")
     ap.add_argument("--pool", default="avg", choices=["avg", "max"])
     ap.add_argument("--pool-kernel", type=int, default=7, help="odd pooling kernel size (the paper uses 7)")
@@ -473,6 +477,10 @@ def main():
 
     L, k_tsp, budget = WORKLOADS[args.workload]
     W = 8
+    if args.length:
+        L = args.length
+        k_tsp, budget = wl.round_half_up(0.2 * L), min(2048, L)
+    tsp = not args.no_tsp
     if args.tsp_rate is not None:
         k_tsp = max(W, wl.round_half_up(args.tsp_rate * L))
     if args.kv_rate is not None:
@@ -482,20 +490,22 @@ def main():
     shape = fk.make_shape(L, pool_mode=args.pool, pool_kernel=args.pool_kernel)
 
     t_gen = time.time()
-    host0 = wl.make_sequence(args.seed, L)
+    host0 = wl.make_sequence(args.seed, L, with_x=tsp)
     sets = []
     for i in range(max(1, args.sets)):
-        h = host0 if i == 0 else wl.make_sequence(args.seed + 1000 + i, L)
-        sets.append({n: dev_bf16(h[n]) for n in ("q_win", "k", "v", "x")})
+        h = host0 if i == 0 else wl.make_sequence(args.seed + 1000 + i, L, with_x=tsp)
+        sets.append({n: (dev_bf16(h[n]) if n in h else None) for n in ("q_win", "k", "v", "x")})
         if i:
             del h
+    if not tsp:
+        k_tsp = 0
     outs = [None] * len(sets)
     t_gen = time.time() - t_gen
 
     def step(i):
         s = sets[i % len(sets)]
         outs[i % len(sets)] = ctx.fkv_compress_kv(shape, s["q_win"], s["k"], s["v"], budget, x=s["x"],
-                                                  k_tsp_per_seq=k_tsp, out=outs[i % len(sets)])
+                                                  k_tsp_per_seq=k_tsp or None, out=outs[i % len(sets)])
 
     def timed(n_steps, first):
         torch.cuda.synchronize()
@@ -548,7 +558,7 @@ def main():
             c, st = lanes[i % 2]
             with torch.cuda.stream(st):
                 outs2[i % len(sets)] = c.fkv_compress_kv(shape, s["q_win"], s["k"], s["v"], budget, x=s["x"],
-                                                         k_tsp_per_seq=k_tsp, out=outs2[i % len(sets)])
+                                                         k_tsp_per_seq=k_tsp or None, out=outs2[i % len(sets)])
 
         for _, st in lanes:
             st.wait_stream(torch.cuda.current_stream())
@@ -625,7 +635,7 @@ def main():
     total_bytes = wl.algorithmic_bytes(L, k_tsp, budget)
     tokens_per_s = L / (wall_ms * 1e-3)
     result = {
-        "metric": "context tokens scored+selected+gathered/sec at L=32K; achieved HBM GB/s vs peak",
+        "metric": "context tokens scored+selected+gathered/sec at L=%s; achieved HBM GB/s vs peak" % ("32K" if L == 32768 else L),
         "value": tokens_per_s,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -642,6 +652,8 @@ def main():
                                                                                   args.pool_kernel, k_tsp, budget, len(sets))},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": dom_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": None if traffic is None else "stored: profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
+                                       "this command, see profiles/hbm_traffic_config2_L32768.md), not measured in this run",
                      "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_us": per_kernel_us[dominant]},
         "path": {"algorithmic_bytes": total_bytes, "achieved_GBps": total_bytes / (wall_ms * 1e-3) / 1e9,
                  "frac_of_peak": total_bytes / (wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -664,8 +676,9 @@ def main():
         o = outs[0]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        ref = oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, args.pool_kernel, args.pool, x=host0["x"],
-                                 k_tsp=k_tsp)
+        hx = host0.get("x")
+        ref = oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, args.pool_kernel, args.pool, x=hx,
+                                 k_tsp=k_tsp or None)
         t_oracle = time.perf_counter() - t0
         if not args.no_cpu_baseline:
             # the first run pays page faults and thread start-up; repeat for about 1.5 s of wall time
@@ -673,12 +686,12 @@ def main():
             reps = max(1, min(20, int(1.5 / max(t_oracle, 1e-3))))
             t0 = time.perf_counter()
             for _ in range(reps):
-                oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, args.pool_kernel, args.pool, x=host0["x"], k_tsp=k_tsp)
+                oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, args.pool_kernel, args.pool, x=hx, k_tsp=k_tsp or None)
             t_mean = (time.perf_counter() - t0) / reps
             n_thr = oracle.max_threads()
             t0 = time.perf_counter()
-            oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, args.pool_kernel, args.pool, x=host0["x"],
-                               k_tsp=k_tsp, threads=1)
+            oracle.compress_kv(host0["q_win"], host0["k"], host0["v"], budget, args.pool_kernel, args.pool, x=hx,
+                               k_tsp=k_tsp or None, threads=1)
             t_single = time.perf_counter() - t0
             oracle.window_attention(host0["q_win"][:, :1], host0["k"][:64, :1], threads=n_thr)  # restore the thread count
             result["cpu_baseline"] = {"value": L / t_mean, "unit": "tokens/s", "cores": n_thr,
@@ -689,12 +702,14 @@ def main():
         if not args.no_parity:
             from parity import assert_index_set
             flips = 0
-            idx_kv, idx_tsp = o["idx_kv"].cpu().numpy(), o["idx_tsp"].cpu().numpy()
+            idx_kv = o["idx_kv"].cpu().numpy()
             for g in range(8):
                 flips += assert_index_set(idx_kv[g], ref["idx_kv"][g], ref["scores_group"][g], W, "bench kv g%d" % g)
                 np.testing.assert_array_equal(host_bits(o["k_out"][g]), host0["k"][idx_kv[g], g])
-            flips += assert_index_set(idx_tsp, ref["idx_tsp"], ref["scores_tsp"], W, "bench tsp")
-            np.testing.assert_array_equal(host_bits(o["x_out"]), host0["x"][idx_tsp])
+            if tsp:
+                idx_tsp = o["idx_tsp"].cpu().numpy()
+                flips += assert_index_set(idx_tsp, ref["idx_tsp"], ref["scores_tsp"], W, "bench tsp")
+                np.testing.assert_array_equal(host_bits(o["x_out"]), host0["x"][idx_tsp])
             result["parity"] = {"index_sets": "match (tolerance-band flips: %d)" % flips, "gathers": "bit-exact"}
     result["setup_s"] = {"input_generation": t_gen}
     print(json.dumps(result))

@@ -148,6 +148,8 @@ def test_repeatability_under_load(L, n_calls):
         for it in range(n_calls // 2):
             outs[0] = call(ctxs[0], sets[it % 3], outs[0])
             check(outs[0], first[it % 3])
+            if it % 100 == 99:   # stop at the first failure: a broken exchange would cost its time limit per call
+                assert ctxs[0].fkv_query_error() == 0 and int(bad) == 0, "after %d calls" % (it + 1)
         torch.cuda.synchronize()
         assert int(bad) == 0
         print("  one stream: ok", flush=True)
@@ -160,6 +162,9 @@ def test_repeatability_under_load(L, n_calls):
                     j = (it + i) % 3
                     outs[i] = call(ctxs[i], sets[j], outs[i])
                     bads[i] += (outs[i]["idx_kv"] != first[j]["idx_kv"]).sum() + (outs[i]["idx_tsp"] != first[j]["idx_tsp"]).sum()
+            if it % 100 == 99:
+                assert all(c.fkv_query_error() == 0 for c in ctxs) and int(bads[0]) == 0 and int(bads[1]) == 0, \
+                    "after %d calls on two streams" % (it + 1)
         torch.cuda.synchronize()
         assert int(bads[0]) == 0 and int(bads[1]) == 0
         for c in ctxs:

@@ -130,6 +130,25 @@ def test_scores_below_fp32_normal_range(ctx, pool_mode):
         assert_index_set(idx[g], oracle.select_topk(rg[g].astype(np.float32), W, k), rg[g], W, "g%d" % g)
 
 
+def test_scores_huge_masked_window_logit(ctx):
+    """The keys of the later window positions are masked for the earlier window rows (causal corner).  A
+    masked key whose logit lies far above everything a row may see must not move that row's softmax
+    reference: the last window key is made 40x a window query here, hundreds of log2 units above the
+    visible logits of rows 0 .. W-2, on both score paths."""
+    print("case: huge masked window-key logit", flush=True)
+    L, W = 600, 8
+    s = wl.make_sequence(12, L, n_heavy=4, with_v=False, with_x=False)
+    qf = wl.bf16_bits_to_f32(s["q_win"])                         # [W, Hq, d]
+    for g in range(8):
+        s["k"][L - 1, g, :] = wl.f32_to_bf16_bits(40.0 * qf[2, 4 * g + 1, :])   # aligned with window row 2 of one head
+    shape = fk.make_shape(L, pool_mode="max")
+    sg, st = ctx.fkv_score_window(shape, dev_bf16(s["q_win"]), dev_bf16(s["k"]))
+    rg, rt = _oracle_batch([s], 7, "max", precision="f64")
+    assert np.isfinite(sg.cpu().numpy()).all()
+    assert_scores_close(sg.cpu().numpy(), rg, "scores_group")
+    assert_scores_close(st.cpu().numpy(), rt, "scores_tsp")
+
+
 def test_scores_ragged_batch(ctx):
     lengths = [300, 1000, 57, 8, 2049, 131]
     print("case: ragged batch", lengths, flush=True)
