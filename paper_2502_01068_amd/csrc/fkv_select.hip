@@ -28,7 +28,6 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
   const int mis = (int)((reinterpret_cast<uintptr_t>(sc) >> 2) & 3);
   const float *base = sc - mis;
   constexpr int kChunk = kSelThreads * kKpt;
-  constexpr int kQ = kKpt / 4;  // 128-bit loads (scan items) per thread
   const int n_chunks = kResident ? 1 : (P + mis + kChunk - 1) / kChunk;
   uint32_t key[kKpt];
   FKV_TICK(0);
