@@ -301,6 +301,19 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
  * the same scores up to fp32 summation order. */
 int fkv_set_score_path(fkv_ctx *ctx, int mode);
 
+/* Which kernels select the top-k of a score row (Sec. 4.2).  0 (default): rows of more than 16384 keys
+ * are cut into at most 8 slices (8192, 16384 or 32768 keys each, by row length), one block per slice,
+ * and the blocks of a row agree on the threshold through device memory inside one launch, when every
+ * block of the call can be resident at once (rows x slices x sequences <= compute units, rows up to
+ * 262144 keys); other calls take one block per row (rows up to 32768 keys) or a chain of launches
+ * (longer rows), and so do all calls while several contexts exist on the device (resident launches of
+ * different contexts are chained, see above).  1: never several blocks per row inside one launch;
+ * 2: several blocks per row whenever the call fits, whatever the row length and the number of
+ * contexts.  All give the same indices.  The resident launch waits on other blocks with the bound of
+ * fkv_set_wait_limit; a wait that runs out raises the context's error flag and the launch writes -1
+ * into every index. */
+int fkv_set_select_path(fkv_ctx *ctx, int mode);
+
 /* How the single-pass score kernel would lay a batch out over at most max_blocks resident blocks
  * (host only; the library plans with the device's compute-unit count).  Block i of sequence b owns the
  * prefix tokens [i * own[b], min(P_b, (i + 1) * own[b])) and computes them plus pool_kernel / 2 halo

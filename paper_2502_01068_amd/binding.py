@@ -24,7 +24,7 @@ EXPORTS = [
     "fkv_profile_kernel_name", "fkv_profile_enable", "fkv_profile_read", "fkv_set_score_path", "fkv_query_error",
     "fkv_score_heads", "fkv_gather_kv_per_head", "fkv_count_from_rate", "fkv_decode_attention",
     "fkv_index_overlap", "fkv_mass_recall", "fkv_gather_kv_paged", "fkv_decode_attention_paged", "fkv_probe_read", "fkv_plan_layer", "fkv_set_wait_limit", "fkv_clear_error", "fkv_compress_kv_paged", "fkv_probe_logits", "fkv_window_output",
-    "fkv_score_window_static", "fkv_score_plan", "fkv_score_window_output",
+    "fkv_score_window_static", "fkv_score_plan", "fkv_score_window_output", "fkv_set_select_path",
 ]
 
 
@@ -95,6 +95,7 @@ def load():
     lib.fkv_count_from_rate.restype = i32
     lib.fkv_count_from_rate.argtypes = [i32, ctypes.c_double]
     lib.fkv_set_score_path.argtypes = [vp, ctypes.c_int]
+    lib.fkv_set_select_path.argtypes = [vp, ctypes.c_int]
     lib.fkv_query_error.argtypes = [vp, pi32]
     lib.fkv_set_wait_limit.argtypes = [vp, i64]
     lib.fkv_clear_error.argtypes = [vp]
@@ -555,6 +556,10 @@ class Context:
     def fkv_set_score_path(self, mode):
         """0 auto, 1 two-pass kernels, 2 single-pass resident-grid kernel."""
         _check(load().fkv_set_score_path(self.handle, int(mode)), "fkv_set_score_path")
+
+    def fkv_set_select_path(self, mode):
+        """0 auto, 1 never several blocks per row in one launch, 2 several blocks per row whenever the call fits."""
+        _check(load().fkv_set_select_path(self.handle, int(mode)), "fkv_set_select_path")
 
     def fkv_set_wait_limit(self, microseconds):
         _check(load().fkv_set_wait_limit(self.handle, int(microseconds)), "fkv_set_wait_limit")

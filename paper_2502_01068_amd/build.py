@@ -6,7 +6,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfastkv_select.so")
-SOURCES = ["fkv_api.hip", "fkv_score.hip", "fkv_score_fused.hip", "fkv_select.hip", "fkv_select_long.hip", "fkv_gather.hip", "fkv_decode.hip", "fkv_diag.hip", "fkv_probe.hip", "fkv_wout.hip"]
+SOURCES = ["fkv_api.hip", "fkv_score.hip", "fkv_score_fused.hip", "fkv_select.hip", "fkv_select_long.hip", "fkv_select_coop.hip", "fkv_gather.hip", "fkv_decode.hip", "fkv_diag.hip", "fkv_probe.hip", "fkv_wout.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -19,7 +19,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-  size_t partial, rowstat, scores_group, scores_tsp, counters, fused_part, fused_lse, sel_long, dec_part, wout_o, wout_ms, total;
+  size_t partial, rowstat, scores_group, scores_tsp, counters, fused_part, fused_lse, sel_long, sel_coop, dec_part, wout_o, wout_ms, total;
   int max_stat_blocks;
 };
 
@@ -36,6 +36,7 @@ WsLayout ws_layout(int64_t max_tokens, int32_t max_seqs) {
   w.fused_part = off;   off += align_up(kFusedPartBytes);
   w.fused_lse = off;    off += align_up(kFusedLseBytes);
   w.sel_long = off;     off += align_up((size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
+  w.sel_coop = off;     off += align_up(kCoopBoxBytes);
   w.dec_part = off;     off += align_up((size_t)max_seqs * kMaxKvHeads * kMaxReal * kDecodeMaxSplits * (kHeadDim + 2) * sizeof(float));
   const size_t wout_slots = (size_t)kWoutBlocks + (size_t)kMaxVGroups * max_seqs;
   w.wout_o = off;       off += align_up(wout_slots * kRowsPerGroup * kHeadDim * sizeof(float));
@@ -58,6 +59,22 @@ struct FusedGate {
   bool recorded = false;
 };
 FusedGate g_gate[16];
+
+// Enqueues a launch whose blocks must all be resident at once, under the device's gate.
+template <typename F>
+hipError_t gated_launch(int device, hipStream_t st, F &&launch) {
+  FusedGate &gate = g_gate[device & 15];
+  std::lock_guard<std::mutex> lock(gate.mu);
+  const bool chained = gate.n_ctx > 1 && gate.last != nullptr;
+  hipError_t e = hipSuccess;
+  if (chained && gate.recorded) e = hipStreamWaitEvent(st, gate.last, 0);
+  if (e == hipSuccess) e = launch();
+  if (e == hipSuccess && chained) {
+    e = hipEventRecord(gate.last, st);
+    gate.recorded = true;
+  }
+  return e;
+}
 
 // Scratch memory and launch parameters the score kernels need besides the caller's tensors: a
 // view of a context's workspace, or of the library's static scratch array.
@@ -87,7 +104,9 @@ struct fkv_ctx {
   uint8_t *ws;
   int n_cu;            // compute units x resident blocks per CU of the single-pass score kernel
   int score_path;      // 0 auto, 1 two-pass kernels, 2 single-pass resident grid
-  unsigned long long wait_ticks;  // bound of the single-pass kernel's grid wait, 100 MHz ticks
+  int n_cu_select;     // resident blocks of the several-blocks-per-row select kernel (0: not available)
+  int select_path;     // 0 auto, 1 never several blocks per row, 2 several blocks per row whenever the launch fits
+  unsigned long long wait_ticks;  // bound of every wait inside a kernel, 100 MHz ticks
   bool prof_on;
   std::vector<EventPair> ev_pool;
   size_t ev_used;
@@ -347,19 +366,10 @@ int enqueue_score(const ScoreWs &w, const fkv_shape *sh, const Resolved &r, cons
       f.err = w.err;
       f.n_wg = total;
       f.timeout_ticks = w.wait_ticks;
-      FusedGate &gate = g_gate[w.device & 15];
-      std::lock_guard<std::mutex> lock(gate.mu);
-      const bool chained = gate.n_ctx > 1 && gate.last != nullptr;
-      hipError_t e = hipSuccess;
-      if (chained && gate.recorded) e = hipStreamWaitEvent(st, gate.last, 0);
-      if (e == hipSuccess) {
+      const hipError_t e = gated_launch(w.device, st, [&] {
         Timed t(w.prof, st, KID_SCORE_FUSED);
-        e = launch_score_fused(a, f, st);
-      }
-      if (e == hipSuccess && chained) {
-        e = hipEventRecord(gate.last, st);
-        gate.recorded = true;
-      }
+        return launch_score_fused(a, f, st);
+      });
       return e == hipSuccess ? FKV_OK : hip_fail(e);
     }
     if (r.sum_p == 0) return FKV_OK;  // no prefix token anywhere: nothing to score
@@ -393,6 +403,29 @@ int enqueue_score(const ScoreWs &w, const fkv_shape *sh, const Resolved &r, cons
   if (e != hipSuccess) return hip_fail(e);
 
   return enqueue_scores_pass2(w, a, r, st);
+}
+
+// The select launch(es) of a call.  Rows long enough take the several-blocks-per-row kernel, whose
+// blocks must all be resident at once (hence the gate).
+hipError_t enqueue_select(fkv_ctx *ctx, const SelectArgs &a, hipStream_t st) {
+  uint32_t *long_state = reinterpret_cast<uint32_t *>(ctx->ws + ctx->lay.sel_long);
+  unsigned *counters = reinterpret_cast<unsigned *>(ctx->ws + ctx->lay.counters);
+  SelectCoop coop{};
+  coop.boxes = reinterpret_cast<unsigned long long *>(ctx->ws + ctx->lay.sel_coop);
+  coop.state = counters + kCtrSelEpoch;
+  coop.err = counters + kCtrError;
+  coop.timeout_ticks = ctx->wait_ticks;
+  coop.max_blocks = std::min(ctx->n_cu_select, kCoopMaxBlocks);
+  coop.mode = ctx->select_path;
+  Timed t(ctx, st, KID_SELECT);
+  if (coop.max_blocks > 0 && coop.mode == 0) {
+    // While several contexts exist on the device, resident launches are chained one after the other;
+    // the select gains less from its resident kernel than concurrent calls lose by that.
+    std::lock_guard<std::mutex> lock(g_gate[ctx->device & 15].mu);
+    if (g_gate[ctx->device & 15].n_ctx > 1) coop.mode = 1;
+  }
+  if (coop.max_blocks <= 0 || coop.mode == 1) return launch_select(a, long_state, nullptr, st);
+  return gated_launch(ctx->device, st, [&] { return launch_select(a, long_state, &coop, st); });
 }
 
 void fill_rowset(SelectRowSet *rs, const float *scores, int64_t stride, int n_rows, int32_t *out,
@@ -490,6 +523,18 @@ size_t fkv_workspace_bytes(int64_t max_total_tokens, int32_t max_seqs) {
   return ws_layout(max_total_tokens, max_seqs).total;
 }
 
+namespace {
+// Mailbox words of the several-blocks-per-row select all stale (tag 0), epoch 1, nobody counted as finished.
+hipError_t reset_select_exchange(fkv_ctx *c) {
+  hipError_t e = hipMemset(c->ws + c->lay.sel_coop, 0, kCoopBoxBytes);
+  const unsigned init[2] = {1u, 0u};
+  static_assert(kCtrSelDone == kCtrSelEpoch + 1, "epoch and finish count are adjacent");
+  if (e == hipSuccess)
+    e = hipMemcpy(c->ws + c->lay.counters + kCtrSelEpoch * sizeof(unsigned), init, sizeof init, hipMemcpyHostToDevice);
+  return e;
+}
+}  // namespace
+
 int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_seqs) {
   if (!out) return FKV_ENULL;
   *out = nullptr;
@@ -520,7 +565,9 @@ int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_
     if (e != hipSuccess) { delete c; return hip_fail(e); }
     const int per_cu = score_fused_max_blocks_per_cu();
     c->n_cu = prop.multiProcessorCount * (per_cu > 0 ? 1 : 0);  // one resident block per CU
+    c->n_cu_select = prop.multiProcessorCount * (select_coop_max_blocks_per_cu() > 0 ? 1 : 0);
   }
+  c->select_path = 0;
   c->prof_on = false;
   c->ev_used = 0;
   c->ev_prev = nullptr;
@@ -540,6 +587,7 @@ int fkv_create(fkv_ctx **out, int device, int64_t max_total_tokens, int32_t max_
   if (e == hipSuccess) e = hipMemset(c->ws + c->lay.counters, 0, kNumCounters * sizeof(unsigned));
   if (e == hipSuccess) e = hipMemset(c->ws + c->lay.fused_part, 0xFF, kFusedPartBytes);  // every mailbox empty
   if (e == hipSuccess) e = hipMemset(c->ws + c->lay.fused_lse, 0xFF, kFusedLseBytes);
+  if (e == hipSuccess) e = reset_select_exchange(c);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipMemset(c->ws + c->lay.sel_long, 0, (size_t)kLongMaxInst * kLongStateWords * sizeof(uint32_t));
   if (e != hipSuccess) {
@@ -602,8 +650,7 @@ int fkv_select_topk(fkv_ctx *ctx, const fkv_shape *shape, const float *scores, i
   for (int b = 0; b <= r.n_seq; ++b) a.cu[b] = r.cu[b];
   fill_rowset(&a.set[0], scores, r.sum_p, n_rows, idx_out, off, r.n_seq);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  Timed t(ctx, st, KID_SELECT);
-  const hipError_t e = launch_select(a, reinterpret_cast<uint32_t *>(ctx->ws + ctx->lay.sel_long), st);
+  const hipError_t e = enqueue_select(ctx, a, st);
   return e == hipSuccess ? FKV_OK : hip_fail(e);
 }
 
@@ -954,8 +1001,7 @@ int fkv_compress_kv_paged(fkv_ctx *ctx, const fkv_shape *shape, const void *q_wi
   a.err = ws_of(ctx).err;
   fill_rowset(&a.set[a.n_sets++], sg, r.sum_p, r.Hkv, idx_kv, g.cnt_off, r.n_seq);
   {
-    Timed t(ctx, st, KID_SELECT);
-    const hipError_t e = launch_select(a, reinterpret_cast<uint32_t *>(ctx->ws + ctx->lay.sel_long), st);
+    const hipError_t e = enqueue_select(ctx, a, st);
     if (e != hipSuccess) return hip_fail(e);
   }
   return enqueue_gather_paged(ctx, r, g, k, v, idx_kv, pg, k_pages, v_pages, st);
@@ -1064,8 +1110,7 @@ int fkv_compress_kv(fkv_ctx *ctx, const fkv_shape *shape, const void *q_win, con
   fill_rowset(&a.set[a.n_sets++], sg, r.sum_p, r.Hkv, idx_kv, off_kv, r.n_seq);
   if (tsp) fill_rowset(&a.set[a.n_sets++], stp, r.sum_p, 1, idx_tsp, off_tsp, r.n_seq);
   {
-    Timed t(ctx, st, KID_SELECT);
-    const hipError_t e = launch_select(a, reinterpret_cast<uint32_t *>(ctx->ws + ctx->lay.sel_long), st);
+    const hipError_t e = enqueue_select(ctx, a, st);
     if (e != hipSuccess) return hip_fail(e);
   }
 
@@ -1158,6 +1203,13 @@ int fkv_set_score_path(fkv_ctx *ctx, int mode) {
   return FKV_OK;
 }
 
+int fkv_set_select_path(fkv_ctx *ctx, int mode) {
+  if (!ctx) return FKV_ENULL;
+  if (mode < 0 || mode > 2) return FKV_EINVAL;
+  ctx->select_path = mode;
+  return FKV_OK;
+}
+
 int fkv_query_error(fkv_ctx *ctx, int32_t *flag_out) {
   if (!ctx || !flag_out) return FKV_ENULL;
   unsigned v = 0;
@@ -1183,6 +1235,7 @@ int fkv_clear_error(fkv_ctx *ctx) {
   // a failed exchange may have left values in the mailboxes: empty them all, then drop the flag
   if (e == hipSuccess) e = hipMemset(ctx->ws + ctx->lay.fused_part, 0xFF, kFusedPartBytes);
   if (e == hipSuccess) e = hipMemset(ctx->ws + ctx->lay.fused_lse, 0xFF, kFusedLseBytes);
+  if (e == hipSuccess) e = reset_select_exchange(ctx);
   if (e == hipSuccess) e = hipMemset(ctx->ws + ctx->lay.counters + kCtrError * sizeof(unsigned), 0, sizeof(unsigned));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   return e == hipSuccess ? FKV_OK : hip_fail(e);

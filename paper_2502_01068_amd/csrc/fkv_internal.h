@@ -152,8 +152,35 @@ struct SelectArgs {
   const unsigned *err;   // sticky error flag of the score pass that produced the rows, or nullptr: while it is
                          // set every index written is -1 (the scores are invalid)
 };
-// `long_state` is the context's state buffer for rows over 32768 keys (may be nullptr).
-hipError_t launch_select(SelectArgs a, uint32_t *long_state, hipStream_t s);
+// Several blocks per row (fkv_select_coop.hip): the blocks of a row exchange histograms and a key list
+// through tagged mailbox words; all blocks of the launch are resident at once.
+constexpr int kCoopHistRounds = 4;    // histogram exchanges a search can need (fixed map, then 3 x 11 bits)
+constexpr int kCoopWords = (kCoopHistRounds + 1) * 1024 + 64;  // mailbox words per block: one region per round, the list, the key range
+constexpr int kCoopMaxSlices = 8;     // slices (blocks) per row; 8192, 16384 or 32768 keys each
+constexpr int kCoopMaxBlocks = 256;   // blocks per launch the mailboxes hold
+constexpr int kCoopMinKeys = 16384;   // rows up to here stay on the one-block kernel (measured: there the exchanges cost more than they save)
+constexpr size_t kCoopBoxBytes = (size_t)kCoopMaxBlocks * kCoopWords * sizeof(unsigned long long);
+constexpr int kCtrSelEpoch = 1;       // context counters: epoch of the next launch (never 0),
+constexpr int kCtrSelDone = 2;        // finish count of the running launch
+struct CoopArgs {
+  unsigned long long *boxes;  // [blocks][kCoopWords]
+  unsigned *state;            // [0] epoch, [1] finish count (low half: blocks done, high half: blocks that failed)
+  unsigned *err;              // the context's sticky error flag
+  unsigned long long timeout_ticks;
+  int blk[FKV_MAX_SEQS + 1];  // first block of sequence b's rows; a row's slices are consecutive blocks
+};
+struct SelectCoop {           // what a context lends to that kernel
+  unsigned long long *boxes;
+  unsigned *state, *err;
+  unsigned long long timeout_ticks;
+  int max_blocks;             // resident blocks (0: the kernel is not used)
+  int mode;                   // 0 rows over kCoopMinKeys keys, 1 never, 2 whenever the launch fits
+};
+int select_coop_max_blocks_per_cu(void);
+bool try_launch_select_coop(const SelectArgs &a, int rows, const SelectCoop &coop, hipStream_t s, hipError_t *e);
+// `long_state` is the context's state buffer for the launch chain that takes rows over 32768 keys (may be
+// nullptr), `coop` what the several-blocks-per-row kernel needs (may be nullptr).
+hipError_t launch_select(SelectArgs a, uint32_t *long_state, const SelectCoop *coop, hipStream_t s);
 int select_long_chunk(void);
 int select_long_threshold(void);
 hipError_t launch_select_long(const SelectArgs &a, int rows, int max_slices, hipStream_t s);

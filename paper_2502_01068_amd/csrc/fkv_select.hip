@@ -216,9 +216,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectArgs a) {
     select_row<false, 32>(sc, P, kp, out, hist, wsum, bcast, scan_tbl);
 }
 
-hipError_t launch_select(SelectArgs a, uint32_t *long_state, hipStream_t s) {
+hipError_t launch_select(SelectArgs a, uint32_t *long_state, const SelectCoop *coop, hipStream_t s) {
   int rows = 0;
   for (int i = 0; i < a.n_sets; ++i) rows += a.set[i].n_rows;
+  {
+    hipError_t e = hipSuccess;
+    a.long_state = nullptr;
+    if (coop != nullptr && try_launch_select_coop(a, rows, *coop, s, &e)) return e;
+  }
   // Rows over one chunk go to the multi-block chain when the call's row instances fit its state.
   int max_slices = 0;
   bool any_short = false;

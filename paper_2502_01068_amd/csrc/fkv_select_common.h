@@ -110,7 +110,9 @@ __device__ __forceinline__ BinPick pick_bin(const uint32_t *hist, uint32_t *wsum
 // keys came before, in index order.  run_gt / run_eq count what earlier chunks kept / saw and are
 // advanced.  scan_tbl: kSelWaves*64*kMaxKpt words, wsum: kSelWaves words, sink: 64 words of LDS.
 // Index order inside a wave is (q, lane, e).  Contains block barriers.
-template <int kKpt>
+// kCoherentOut: the indices leave as agent-scope atomic stores (straight to device memory instead of
+// resting in the writing CU's L2), for kernels whose blocks order their output among themselves.
+template <int kKpt, bool kCoherentOut = false>
 __device__ __forceinline__ void compact_chunk(const uint32_t (&key)[kKpt], uint32_t T, uint32_t need_eq,
                                               uint32_t &run_gt, uint32_t &run_eq, int i_chunk, int32_t *out,
                                               uint32_t *scan_tbl, uint32_t *wsum, uint32_t *sink) {
@@ -182,7 +184,12 @@ __device__ __forceinline__ void compact_chunk(const uint32_t (&key)[kKpt], uint3
       }
     }
     wave_sync_lds();
-    for (uint32_t o = lane; o < wave_end - wave_base; o += 64) out[wave_base + o] = stg[o];
+    for (uint32_t o = lane; o < wave_end - wave_base; o += 64) {
+      if (kCoherentOut)
+        __hip_atomic_store(out + wave_base + o, stg[o], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else
+        out[wave_base + o] = stg[o];
+    }
     __syncthreads();  // the tables are rewritten by the next chunk
     run_gt += total & 0xFFFFu;
     run_eq += total >> 16;

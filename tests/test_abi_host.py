@@ -149,6 +149,7 @@ def test_entry_points_validate_before_touching_the_context(lib):
     assert lib.fkv_probe_read(None, p16, 1000, 0, None) == fk.FKV_EINVAL and lib.fkv_probe_read(None, p16, 65536, 0, None) == fk.FKV_ENULL
     assert lib.fkv_set_wait_limit(None, 5) == fk.FKV_ENULL and lib.fkv_clear_error(None) == fk.FKV_ENULL
     assert lib.fkv_destroy(None) == fk.FKV_ENULL
+    assert lib.fkv_set_select_path(None, 0) == fk.FKV_ENULL
     assert lib.fkv_set_score_path(None, 0) == fk.FKV_ENULL and lib.fkv_query_error(None, None) == fk.FKV_ENULL
 
 

@@ -11,13 +11,16 @@ from parity import assert_index_set, assert_scores_close, dev_bf16, host_bits
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module", params=["auto", "two_pass"])
+@pytest.fixture(scope="module", params=["auto", "two_pass", "coop_select"])
 def ctx(request):
-    """Every case runs twice: with the default score path (the single-pass resident-grid kernel
-    whenever the batch fits, which all cases of this file do) and with the two-pass kernels."""
+    """Every case runs three times: with the default paths (the single-pass resident-grid score kernel
+    whenever the batch fits, which all cases of this file do; one select block per row up to 16384
+    keys, several above), with the two-pass score kernels, and with the several-blocks-per-row select forced for every
+    call whose blocks fit the device (rows of any length, down to one slice)."""
     c = fk.Context(max_total_tokens=140000, max_seqs=16)
-    c.fkv_set_score_path(0 if request.param == "auto" else 1)
-    print("score path:", request.param, flush=True)
+    c.fkv_set_score_path(1 if request.param == "two_pass" else 0)
+    c.fkv_set_select_path(2 if request.param == "coop_select" else 0)
+    print("paths:", request.param, flush=True)
     yield c
     assert c.fkv_query_error() == 0
     c.close()
@@ -263,6 +266,106 @@ def test_select_ragged(ctx):
             np.testing.assert_array_equal(idx[r, o:o + k], oracle.select_topk(scores[r, col:col + P], W, k))
         col += P
         o += k
+
+
+@pytest.mark.parametrize("P,rows,ks", [
+    (8189, 3, [8, 9, 1000, 8197]), (8190, 2, [4000]), (16384, 9, [2048]), (16385, 9, [16393]),
+    (24573, 5, [5000]), (32760, 9, [8, 2048, 6554, 32768]), (49152, 9, [9838]), (131064, 9, [13107, 26214]),
+    (262136, 7, [8, 50000]),   # 8 slices of 32768 keys per row
+])
+def test_select_several_blocks_per_row(P, rows, ks):
+    """Rows cut into slices, one block each, that agree on the threshold inside one launch: bit-exact
+    against the oracle with score-like values (spread over many powers of two), heavy ties, a constant
+    row, a two-valued row, a row that is mostly zeros, and a row of both signs whose range spans all of
+    fp32 (four histogram exchanges)."""
+    W = 8
+    print("case: select, several blocks per row, P=%d rows=%d ks=%s" % (P, rows, ks), flush=True)
+    rng = np.random.default_rng(P + rows)
+    scores = np.exp(4.0 * rng.standard_normal((rows, P))).astype(np.float32) * np.float32(8.0 / P)
+    scores[0] = wl.random_scores(P % 977, 1, P, ties=0.5)[0]
+    if rows > 1:
+        scores[1, :] = np.float32(0.125)
+    if rows > 2:
+        scores[2] = np.where(rng.random(P) < 0.3, np.float32(0.75), np.float32(0.25))
+    if rows > 3:
+        scores[3, rng.random(P) < 0.97] = 0.0
+    if rows > 4:
+        scores[4] = rng.standard_normal(P).astype(np.float32) * np.float32(1000.0)
+        scores[4, ::5] = np.float32(1e-30) * rng.random(len(scores[4, ::5])).astype(np.float32)
+    c = fk.Context(max_total_tokens=P + W, max_seqs=1)
+    try:
+        d = torch.from_numpy(scores).cuda()
+        shape = fk.make_shape(P + W)
+        for path in (2, 1):
+            c.fkv_set_select_path(path)
+            for k in ks:
+                idx = c.fkv_select_topk(shape, d, k).cpu().numpy()
+                for r in range(rows):
+                    np.testing.assert_array_equal(idx[r], oracle.select_topk(scores[r], W, k),
+                                                  err_msg="path %d row %d k %d" % (path, r, k))
+        assert c.fkv_query_error() == 0
+    finally:
+        c.close()
+
+
+def test_select_several_blocks_ragged_batch():
+    """Several sequences of different lengths in one resident launch (slice counts differ per sequence)."""
+    lengths = [20000, 9000, 33000, 8, 50]
+    ks = [4000, 8, 33000, 8, 20]
+    print("case: select, several blocks per row, ragged", lengths, ks, flush=True)
+    W, rows = 8, 5
+    sum_p = sum(lengths) - W * len(lengths)
+    scores = wl.random_scores(78, rows, sum_p, ties=0.3)
+    shape = fk.make_shape(lengths)
+    c = fk.Context(max_total_tokens=sum(lengths), max_seqs=len(lengths))
+    try:
+        c.fkv_set_select_path(2)
+        for _ in range(3):   # back-to-back launches: the epoch moves on, stale mailbox words are ignored
+            idx = c.fkv_select_topk(shape, torch.from_numpy(scores).cuda(), ks).cpu().numpy()
+            col, o = 0, 0
+            for L, k in zip(lengths, ks):
+                P = L - W
+                for r in range(rows):
+                    np.testing.assert_array_equal(idx[r, o:o + k], oracle.select_topk(scores[r, col:col + P], W, k))
+                col += P
+                o += k
+        assert c.fkv_query_error() == 0
+    finally:
+        c.close()
+
+
+def test_select_exchange_gives_up_cleanly_and_recovers():
+    """Failure path of the several-blocks-per-row select, forced from the host with a wait limit of
+    1 us: blocks that have to wait give up, the flag is raised, the launch ends normally with -1 in
+    every index; after fkv_clear_error with the limit restored the next call is correct."""
+    print("case: select exchange wait limit", flush=True)
+    P, W, rows, k = 65536 - 8, 8, 9, 5000
+    scores = wl.random_scores(5, rows, P, ties=0.1)
+    c = fk.Context(max_total_tokens=P + W, max_seqs=1)
+    try:
+        d = torch.from_numpy(scores).cuda()
+        shape = fk.make_shape(P + W)
+        c.fkv_set_select_path(2)
+        want = c.fkv_select_topk(shape, d, k).clone()
+        assert c.fkv_query_error() == 0
+        c.fkv_set_wait_limit(1)
+        failed = 0
+        for _ in range(5):
+            bad = c.fkv_select_topk(shape, d, k)
+            if c.fkv_query_error() == 1:
+                failed += 1
+                assert (bad == -1).all()   # the failure is visible in the output
+                c.fkv_clear_error()
+            else:                          # every wait happened to be over in time: then the result is right
+                assert torch.equal(bad, want)
+        print("  launches that gave up: %d of 5" % failed, flush=True)
+        assert failed >= 1
+        c.fkv_set_wait_limit(0)
+        for _ in range(2):
+            assert torch.equal(c.fkv_select_topk(shape, d, k), want)
+        assert c.fkv_query_error() == 0
+    finally:
+        c.close()
 
 
 # ------------------------------------------------------------------------------------ gathers
