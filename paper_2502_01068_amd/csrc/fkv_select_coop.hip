@@ -37,7 +37,8 @@ static_assert(kCoopHeader + 2 <= kCoopWords, "mailbox regions");
 
 __host__ __device__ inline int coop_slices(int P, int chunk) { return P + 3 <= chunk ? 1 : (P + 3 + chunk - 1) / chunk; }
 
-template <int kKpt>
+// kKpt: keys per thread; kSl: most slices a row of the launch has (sizes the unrolled exchange code)
+template <int kKpt, int kSl>
 __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopArgs c) {
   constexpr int kChunk = kSelThreads * kKpt;  // keys per block
   __shared__ uint32_t hist[kBins + 32];  // + one spare word per bank for key slots that are not counted
@@ -140,11 +141,11 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
     // With every slice's histogram word of this thread's bin pair in w[] (own slice included): stages them,
     // picks the bin of the `remaining`-th largest key of the row and updates remaining, n_in, own_in,
     // in_before, gt_before.  `failed`: this wave's fetch ran out.  False if any wave's did.
-    auto pick = [&](const uint32_t (&w)[kCoopMaxSlices], bool failed, uint32_t &digit) -> bool {
+    auto pick = [&](const uint32_t (&w)[kSl], bool failed, uint32_t &digit) -> bool {
       uint32_t *stage = scan_tbl;
       uint32_t tot0 = 0, tot1 = 0, bef0 = 0, bef1 = 0;
 #pragma unroll
-      for (int j = 0; j < kCoopMaxSlices; ++j)
+      for (int j = 0; j < kSl; ++j)
         if (j < M) {
           stage[j * kSelThreads + tid] = w[j];
           tot0 += w[j] & 0xFFFFu;
@@ -181,9 +182,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
       for (int j = 0; j < s; ++j) in_before += slice_cnt[j];
       return true;
     };
-    // Finishes the search inside [lo, lo + span] on keys held in registers (cand[j], j < n_c; keys outside the
-    // interval and empty slots take no part): sets lo to the threshold key; whole = every key >= lo is kept.
-    auto finish_on_list = [&](const uint32_t (&cand)[kCoopMaxSlices], int n_c, bool &whole) {
+    // Finishes the search inside [lo, lo + span] on the list (one key per thread; 0 = none, keys outside the
+    // interval take no part): sets lo to the threshold key; whole = every key >= lo is kept.
+    auto finish_on_list = [&](uint32_t cand, bool &whole) {
       whole = false;
       if (span > 0u) {
         // first pass over 8192 bins (behind the staged histogram words): with a few hundred keys in the interval
@@ -195,10 +196,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
         *reinterpret_cast<u32x4 *>(wide + 8 * tid) = u32x4{0u, 0u, 0u, 0u};
         *reinterpret_cast<u32x4 *>(wide + 8 * tid + 4) = u32x4{0u, 0u, 0u, 0u};
         __syncthreads();
-#pragma unroll
-        for (int j = 0; j < kCoopMaxSlices; ++j) {
-          const uint32_t rel = cand[j] - lo;  // below lo, or an empty slot (key 0): wraps above span
-          if (j < n_c && rel <= span) atomicAdd(&wide[rel >> shift], 1u);
+        {
+          const uint32_t rel = cand - lo;  // below lo, or an empty slot (key 0): wraps above span
+          if (rel <= span) atomicAdd(&wide[rel >> shift], 1u);
         }
         __syncthreads();
         const u32x4 lo4 = *reinterpret_cast<const u32x4 *>(wide + 8 * grp), hi4 = *reinterpret_cast<const u32x4 *>(wide + 8 * grp + 4);
@@ -232,10 +232,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
       while (span > 0u && !whole) {
         const int shift = max(32 - __clz(span) - 11, 0);
         clear_hist();
-#pragma unroll
-        for (int j = 0; j < kCoopMaxSlices; ++j) {
-          const uint32_t rel = cand[j] - lo;  // below lo, or an empty slot (key 0): wraps above span
-          if (j < n_c && rel <= span) atomicAdd(&hist[rel >> shift], 1u);
+        {
+          const uint32_t rel = cand - lo;
+          if (rel <= span) atomicAdd(&hist[rel >> shift], 1u);
         }
         __syncthreads();
         const BinPick p = pick_bin(hist, wsum, bcast, remaining);
@@ -287,7 +286,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
       span = kmax - kmin;  // every key of the row lies in [lo, lo + span]
     }
     FKV_TICK(1);
-    uint32_t w[kCoopMaxSlices];
+    uint32_t w[kSl];
     uint32_t digit;
 
     uint32_t T, need_eq, eq_before = 0;
@@ -306,9 +305,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
         break;
       }
       if (n_in <= (uint32_t)kCoopCandCap) {
-        uint32_t cand[kCoopMaxSlices];
-        int cand_sl[kCoopMaxSlices];  // slice a candidate came from
-        int n_c;
+        uint32_t cand = 0;  // this thread's key of the list
+        int my_sl = 0;      // and the slice it came from
         const uint32_t lo_list = lo, span_list = span;
         {
           // ---- the list: every slice posts its keys of the interval, every block reads them all
@@ -326,23 +324,18 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
             for (int e = 0; e < kKpt; ++e)
               if (key[e] - lo <= span && at < (uint32_t)kCoopCandCap) tag_post(my_box + kCoopList + at++, epoch, key[e]);
           }
-          n_c = 1;
-#pragma unroll
-          for (int j = 0; j < kCoopMaxSlices; ++j) { cand[j] = 0; cand_sl[j] = 0; }
           const bool valid = (uint32_t)tid < n_in;
           uint32_t off = 0;
-          int my_sl = 0;
           if (valid)
             for (; my_sl < M - 1; ++my_sl) {
               const uint32_t n = slice_cnt[my_sl];
               if ((uint32_t)tid < off + n) break;
               off += n;
             }
-          cand_sl[0] = my_sl;
           uint32_t one[1] = {0u};
           const bool got_it = fetch([&](int) { return row_box + (size_t)my_sl * kCoopWords + kCoopList + ((uint32_t)tid - off); },
                                     [&](int) { return !valid; }, one);
-          cand[0] = one[0];
+          cand = one[0];
           if (!got_it && lane == 0) misc[3] = 1u;
           __syncthreads();
           if (misc[3] != 0u) return false;
@@ -350,16 +343,12 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
         FKV_TICK(3);
         FKV_BTICK(2);
         bool whole;
-        finish_on_list(cand, n_c, whole);
+        finish_on_list(cand, whole);
         // list keys of the earlier slices (inside the interval the list was made for) that are kept for sure /
         // that tie with the threshold
-        uint32_t n_kept = 0, n_tied = 0;
-#pragma unroll
-        for (int j = 0; j < kCoopMaxSlices; ++j) {
-          const bool early = j < n_c && cand_sl[j] < s && cand[j] - lo_list <= span_list;
-          n_kept += (early && (whole ? cand[j] >= lo : cand[j] > lo)) ? 1u : 0u;
-          n_tied += (early && !whole && cand[j] == lo) ? 1u : 0u;
-        }
+        const bool early = my_sl < s && cand - lo_list <= span_list;
+        uint32_t n_kept = (early && (whole ? cand >= lo : cand > lo)) ? 1u : 0u;
+        const uint32_t n_tied = (early && !whole && cand == lo) ? 1u : 0u;
         n_kept = wave_sum_to_last(n_kept | (n_tied << 16));
         if (lane == 63 && n_kept != 0u) {
           atomicAdd(&misc[1], n_kept & 0xFFFFu);
@@ -394,7 +383,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
       const bool got_all = fetch([&](int j) { return row_box + (size_t)j * kCoopWords + round * kSelThreads + tid; },
                                  [&](int j) { return j >= M || j == s; }, w);
 #pragma unroll
-      for (int j = 0; j < kCoopMaxSlices; ++j)
+      for (int j = 0; j < kSl; ++j)
         if (j == s) w[j] = mine_r;
       if (!pick(w, !got_all, digit)) return false;
       lo += digit << shift;
@@ -449,7 +438,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
 
 int select_coop_max_blocks_per_cu(void) {
   int n = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_select_coop<32>, kSelThreads, 0) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_select_coop<32, kCoopMaxSlices>, kSelThreads, 0) != hipSuccess) return 0;
   return n;
 }
 
@@ -477,12 +466,14 @@ bool try_launch_select_coop(const SelectArgs &a, int rows, const SelectCoop &coo
   c.state = coop.state;
   c.err = coop.err;
   c.timeout_ticks = coop.timeout_ticks;
-  if (kpt == 8)
-    hipLaunchKernelGGL(k_select_coop<8>, dim3((unsigned)total), dim3(kSelThreads), 0, s, a, c);
+  if (kpt == 8 && coop_slices(max_p, kSelThreads * kpt) <= 4)
+    hipLaunchKernelGGL((k_select_coop<8, 4>), dim3((unsigned)total), dim3(kSelThreads), 0, s, a, c);
+  else if (kpt == 8)
+    hipLaunchKernelGGL((k_select_coop<8, kCoopMaxSlices>), dim3((unsigned)total), dim3(kSelThreads), 0, s, a, c);
   else if (kpt == 16)
-    hipLaunchKernelGGL(k_select_coop<16>, dim3((unsigned)total), dim3(kSelThreads), 0, s, a, c);
+    hipLaunchKernelGGL((k_select_coop<16, kCoopMaxSlices>), dim3((unsigned)total), dim3(kSelThreads), 0, s, a, c);
   else
-    hipLaunchKernelGGL(k_select_coop<32>, dim3((unsigned)total), dim3(kSelThreads), 0, s, a, c);
+    hipLaunchKernelGGL((k_select_coop<32, kCoopMaxSlices>), dim3((unsigned)total), dim3(kSelThreads), 0, s, a, c);
   *e = hipGetLastError();
   return true;
 }
