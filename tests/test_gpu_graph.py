@@ -65,14 +65,17 @@ def test_compress_kv_graph_replays_match_eager(score_path):
     ctx.close()
 
 
-def test_serving_step_graph_replays_match_eager():
+@pytest.mark.parametrize("select_path", [0, 1])
+def test_serving_step_graph_replays_match_eager(select_path):
     """A serving-style step recorded as one graph: the window rows' attention output, KVCompress into a
-    paged cache, decode over the pages, and a long-row select (the multi-launch chain); replays with
-    changed inputs must match eager runs."""
-    print("case: graph capture of paged compress + paged decode + long select", flush=True)
+    paged cache, decode over the pages, and a long-row select (several blocks per row inside one launch,
+    whose mailbox epoch lives in device memory and so moves on with every replay; or the multi-launch
+    chain); replays with changed inputs must match eager runs."""
+    print("case: graph capture of paged compress + paged decode + long select, select path %d" % select_path, flush=True)
     L, budget, ps, Hkv = 6000, 512, 16, 8
     n_pages = budget // ps + 9
     ctx = fk.Context(max_total_tokens=40008, max_seqs=1)
+    ctx.fkv_set_select_path(select_path)
     shape = fk.make_shape(L, pool_mode="avg")
     long_shape = fk.make_shape(40008)
     rng = np.random.default_rng(3)
