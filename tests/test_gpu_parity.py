@@ -625,13 +625,18 @@ def test_grid_wait_gives_up_cleanly_and_recovers():
         c.close()
 
 
-def test_two_contexts_on_two_streams():
-    """Two calls in flight: two contexts, two streams, single-pass score launches chained on the GPU.
-    Every interleaved call must reproduce the result of the same call run alone, bit for bit."""
-    print("case: two contexts on two streams", flush=True)
-    L, budget, k_tsp = 12000, 512, 2400
+@pytest.mark.parametrize("select_path", [0, 2])
+def test_two_contexts_on_two_streams(select_path):
+    """Two calls in flight: two contexts, two streams, resident-grid launches chained on the GPU (the
+    single-pass score kernel; with select path 2 also the several-blocks-per-row select, which the
+    default path leaves alone while two contexts exist).  Every interleaved call must reproduce the
+    result of the same call run alone, bit for bit."""
+    print("case: two contexts on two streams, select path %d" % select_path, flush=True)
+    L, budget, k_tsp = 20000, 512, 4000
     seqs = [wl.make_sequence(31 + i, L) for i in range(2)]
     ctxs = [fk.Context(max_total_tokens=L, max_seqs=1) for _ in range(2)]
+    for c in ctxs:
+        c.fkv_set_select_path(select_path)
     streams = [torch.cuda.Stream() for _ in range(2)]
     try:
         shape = fk.make_shape(L, pool_mode="avg")

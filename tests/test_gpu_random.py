@@ -50,12 +50,15 @@ def test_random_select(ctx, case):
     Ps = [int(rng.choice(edges)) if rng.random() < 0.5 else int(rng.integers(0, 50000)) for _ in range(B)]
     rows = int(rng.integers(1, 5))
     ks = [int(rng.integers(W, P + W + 1)) for P in Ps]
-    print("case %d: W=%d P=%s rows=%d ks=%s" % (case, W, Ps, rows, ks), flush=True)
+    path = (0, 2, 1)[case % 3]   # default / several blocks per row wherever they fit / never
+    ctx.fkv_set_select_path(path)
+    print("case %d: W=%d P=%s rows=%d ks=%s select path %d" % (case, W, Ps, rows, ks, path), flush=True)
     scores = np.concatenate([np.stack([_score_row(rng, P, int(rng.integers(0, 6))) for _ in range(rows)]) for P in Ps],
                             axis=1) if sum(Ps) else np.zeros((rows, 0), np.float32)
     lengths = [P + W for P in Ps]
     shape = fk.make_shape(lengths if B > 1 else lengths[0], window=W)
     idx = ctx.fkv_select_topk(shape, torch.from_numpy(np.ascontiguousarray(scores)).cuda(), ks).cpu().numpy()
+    ctx.fkv_set_select_path(0)
     col = o = 0
     for P, k in zip(Ps, ks):
         for r in range(rows):
@@ -92,6 +95,7 @@ def test_random_fused_call_equals_its_steps(ctx, case):
     hidden = 16 * int(rng.integers(1, 20))
     pool_mode = ("max", "avg")[case % 2]
     ctx.fkv_set_score_path(case % 3 if case % 3 != 2 else 0)
+    ctx.fkv_set_select_path(2 if case % 4 >= 2 else 0)   # half the cases: several select blocks per row wherever they fit
     print("case %d: lengths=%s budgets=%s ktsps=%s hidden=%d %s" % (case, lengths, budgets, ktsps, hidden, pool_mode), flush=True)
     batch = wl.make_batch(5000 + case, lengths, n_heavy=5, hidden=hidden)
     shape = fk.make_shape(lengths if B > 1 else lengths[0], pool_mode=pool_mode)
@@ -103,6 +107,7 @@ def test_random_fused_call_equals_its_steps(ctx, case):
     ko, vo = ctx.fkv_gather_kv(shape, k, v, idx_kv, budgets)
     xo = ctx.fkv_gather_rows(shape, x, idx_tsp, ktsps)
     ctx.fkv_set_score_path(0)
+    ctx.fkv_set_select_path(0)
     assert torch.equal(out["idx_kv"], idx_kv) and torch.equal(out["idx_tsp"], idx_tsp)
     for a, b in ((out["k_out"], ko), (out["v_out"], vo), (out["x_out"], xo)):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
