@@ -16,8 +16,10 @@
 //             each for itself and with the same result
 //   compact   with the threshold and the per-slice counts every block knows where its kept indices
 //             start in the output and writes them in index order.
-// Three exchanges in the usual case, each about one trip through device memory (2.5 us), against one
-// launch per step (5 us each) in the launch chain this kernel replaces where the rows fit.
+// Three exchanges in the usual case, 2-4 us each (a post and a poll are one trip through device memory
+// each, and a poll that comes too early costs another), against one launch per step (5 us each) in the
+// launch chain this kernel replaces where the rows fit.  Histogram region 0 of the mailboxes is unused
+// (rounds count from 1).
 //
 // Every wait is bounded.  A block that gives up raises the context's error flag and marks the launch
 // as failed; the block that finishes last then overwrites every index of the launch with -1.  So
