@@ -439,6 +439,10 @@ def main():
                     "(k_tsp = round-half-up(0.2 L), kv budget = min(2048, L)); e.g. 6554 is a layer after the TSP layer")
     ap.add_argument("--no-tsp", action="store_true", help="single-sequence workloads: KVCompress only (no TSP leg, no hidden rows)")
     ap.add_argument("--budget", type=int, default=0, help="config4_ragged: KV budget per KV head (default: sweep 512, 1024, 2048)")
+    ap.add_argument("--score-path", type=int, default=0, choices=[0, 1, 2], help="single-sequence workloads: 0 default, "
+                    "1 two-pass score kernels, 2 single-pass kernel or fail (fkv_set_score_path)")
+    ap.add_argument("--select-path", type=int, default=0, choices=[0, 1, 2], help="single-sequence workloads: 0 default, "
+                    "1 never several select blocks per row, 2 several whenever they fit (fkv_set_select_path)")
     ap.add_argument("--pool", default="avg", choices=["avg", "max"])
     ap.add_argument("--pool-kernel", type=int, default=7, help="odd pooling kernel size (the paper uses 7)")
     ap.add_argument("--chain-length", type=int, default=32768, help="context length of config5_chain (the paper's "
@@ -487,6 +491,8 @@ def main():
         budget = max(W, wl.round_half_up(args.kv_rate * L))
     torch.cuda.set_device(0)
     ctx = fk.Context(max_total_tokens=L, max_seqs=1, device=0)
+    ctx.fkv_set_score_path(args.score_path)
+    ctx.fkv_set_select_path(args.select_path)
     shape = fk.make_shape(L, pool_mode=args.pool, pool_kernel=args.pool_kernel)
 
     t_gen = time.time()
@@ -648,8 +654,10 @@ def main():
         "dtype": "bf16 inputs, fp32 accumulate and scores, int32 indices",
         "data": "synthetic (seeded N(0,1) bf16 + 1% planted heavy keys)",
         "config": {"workload": "%s: 1 layer, batch 1, L=%d, 32 q / 8 kv heads, d=128, hidden 4096, W=8, pool %s %d, "
-                               "k_tsp=%d, kv budget=%d, %d rotating input sets" % (args.workload, L, args.pool,
-                                                                                  args.pool_kernel, k_tsp, budget, len(sets))},
+                               "k_tsp=%d, kv budget=%d, %d rotating input sets%s" % (
+                                   args.workload, L, args.pool, args.pool_kernel, k_tsp, budget, len(sets),
+                                   "" if not (args.score_path or args.select_path) else
+                                   ", score path %d, select path %d" % (args.score_path, args.select_path))},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": dom_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "traffic_source": None if traffic is None else "stored: profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
