@@ -120,24 +120,50 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
     // until all carry this launch's epoch; payloads to `got`.  Wave-uniform result.
     auto fetch = [&](auto slot, auto skip, auto &got) -> bool {
       constexpr int kN = (int)(sizeof(got) / sizeof(got[0]));
-      unsigned pending = 0;
-#pragma unroll
-      for (int i = 0; i < kN; ++i)
-        if (!skip(i)) pending |= 1u << i;
       BoundedWait wait(c.timeout_ticks);
-      while (true) {
-        unsigned long long v[kN];
+      if constexpr (kKpt >= 32 && kN > 4) {
+        // 32 keys per thread leave few registers: four words in flight at a time
 #pragma unroll
-        for (int i = 0; i < kN; ++i)
-          if (pending & (1u << i)) v[i] = tag_peek(slot(i));
+        for (int p0 = 0; p0 < kN; p0 += 4) {
+          unsigned pending = 0;
 #pragma unroll
-        for (int i = 0; i < kN; ++i)
-          if ((pending & (1u << i)) && tag_is(v[i], epoch)) {
-            got[i] = (uint32_t)v[i];
-            pending &= ~(1u << i);
+          for (int i = 0; i < 4; ++i)
+            if (p0 + i < kN && !skip(p0 + i)) pending |= 1u << i;
+          while (true) {
+            unsigned long long v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (pending & (1u << i)) v[i] = tag_peek(slot(p0 + i));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if ((pending & (1u << i)) && tag_is(v[i], epoch)) {
+                got[p0 + i] = (uint32_t)v[i];
+                pending &= ~(1u << i);
+              }
+            if (!__any(pending != 0u)) break;
+            if (wait.expired()) return false;
           }
-        if (!__any(pending != 0u)) return true;
-        if (wait.expired()) return false;
+        }
+        return true;
+      } else {
+        unsigned pending = 0;
+#pragma unroll
+        for (int i = 0; i < kN; ++i)
+          if (!skip(i)) pending |= 1u << i;
+        while (true) {
+          unsigned long long v[kN];
+#pragma unroll
+          for (int i = 0; i < kN; ++i)
+            if (pending & (1u << i)) v[i] = tag_peek(slot(i));
+#pragma unroll
+          for (int i = 0; i < kN; ++i)
+            if ((pending & (1u << i)) && tag_is(v[i], epoch)) {
+              got[i] = (uint32_t)v[i];
+              pending &= ~(1u << i);
+            }
+          if (!__any(pending != 0u)) return true;
+          if (wait.expired()) return false;
+        }
       }
     };
     // With every slice's histogram word of this thread's bin pair in w[] (own slice included): stages them,
