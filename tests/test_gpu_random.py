@@ -41,13 +41,14 @@ def _score_row(rng, P, kind):
     return np.full(P, np.float32(rng.standard_normal()), np.float32)   # constant row
 
 
-@pytest.mark.parametrize("case", range(40))
+@pytest.mark.parametrize("case", range(120))
 def test_random_select(ctx, case):
     rng = np.random.default_rng(3000 + case)
     W = int(rng.integers(1, 9))
     B = int(rng.integers(1, 4))
     edges = [1, 63, 64, 1023, 1024, 1025, 8191, 8192, 8193, 16383, 16385, 32765, 32766, 32767, 40000, 70000]
-    Ps = [int(rng.choice(edges)) if rng.random() < 0.5 else int(rng.integers(0, 50000)) for _ in range(B)]
+    top = 50000 if case < 40 else int(rng.choice([20000, 90000, 260000])) // B   # later cases: rows up to 8 slices of 32768 keys
+    Ps = [int(rng.choice(edges)) if rng.random() < 0.5 else int(rng.integers(0, top)) for _ in range(B)]
     rows = int(rng.integers(1, 5))
     ks = [int(rng.integers(W, P + W + 1)) for P in Ps]
     path = (0, 2, 1)[case % 3]   # default / several blocks per row wherever they fit / never
