@@ -117,9 +117,11 @@ def test_config4_ragged(budget):
 @pytest.mark.parametrize("L,n_calls", [(32768, 1500), (61440, 600)])
 def test_repeatability_under_load(L, n_calls):
     """The single-pass kernel's grid exchange (both register-capacity variants), its LDS-direct K
-    stream and the select's tie handling must not depend on timing: back-to-back calls over 3 rotating
-    input sets, two contexts alternating on two streams for the second half, every output compared
-    with the first call's on the device."""
+    stream, the exchanges of the several-blocks-per-row select and the tie handling must not depend on
+    timing: back-to-back calls over 3 rotating input sets (one context: the default paths, i.e. both
+    resident-grid kernels), then two contexts alternating on two streams (every other call with the
+    resident select forced, so that it also runs chained behind the other context's launches), every
+    output compared with the first call's on the device."""
     print("case: repeatability L=%d, %d calls" % (L, n_calls), flush=True)
     k_tsp, budget = wl.round_half_up(0.2 * L), 2048
     shape = fk.make_shape(L, pool_mode="max")
@@ -131,7 +133,7 @@ def test_repeatability_under_load(L, n_calls):
                          k=torch.randn((L, 8, 128), device="cuda", generator=gen).bfloat16(),
                          v=torch.randn((L, 8, 128), device="cuda", generator=gen).bfloat16(),
                          x=torch.randn((L, 4096), device="cuda", generator=gen).bfloat16()))
-    ctxs = [fk.Context(max_total_tokens=L, max_seqs=1) for _ in range(2)]
+    ctxs = [fk.Context(max_total_tokens=L, max_seqs=1)]   # the second one is created for the second half
     streams = [torch.cuda.Stream() for _ in range(2)]
     try:
         def call(c, s, out=None):
@@ -153,6 +155,7 @@ def test_repeatability_under_load(L, n_calls):
         torch.cuda.synchronize()
         assert int(bad) == 0
         print("  one stream: ok", flush=True)
+        ctxs.append(fk.Context(max_total_tokens=L, max_seqs=1))
         bads = [torch.zeros((), dtype=torch.int64, device="cuda") for _ in range(2)]
         for st in streams:
             st.wait_stream(torch.cuda.current_stream())
@@ -160,6 +163,7 @@ def test_repeatability_under_load(L, n_calls):
             for i in (0, 1):
                 with torch.cuda.stream(streams[i]):
                     j = (it + i) % 3
+                    ctxs[i].fkv_set_select_path(2 if it % 2 else 0)
                     outs[i] = call(ctxs[i], sets[j], outs[i])
                     bads[i] += (outs[i]["idx_kv"] != first[j]["idx_kv"]).sum() + (outs[i]["idx_tsp"] != first[j]["idx_tsp"]).sum()
             if it % 100 == 99:
