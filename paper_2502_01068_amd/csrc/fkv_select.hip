@@ -83,7 +83,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
 
   uint32_t n_cand = 0xFFFFFFFFu;
   if (s > 0) {
-    // round 1: every key of the row
+    // first pass: every key of the row
     const int shift = s - min(11, s);
     clear_hist();
     for (int ch = 0; ch < n_chunks; ++ch) {
@@ -153,7 +153,7 @@ __device__ __forceinline__ void select_row(const float *sc, int P, int kp, int32
       for (int ch = 0; ch < n_chunks; ++ch) {
         if (!kResident) load_keys<kKpt>(base, mis, P, ch * kChunk, wave, lane, key);
 #pragma unroll
-        for (int e = 0; e < kKpt; ++e) {  // keys equal to lo are left to pick_bin's total, as in round 1
+        for (int e = 0; e < kKpt; ++e) {  // keys equal to lo are left to pick_bin's total, as in the first pass
           const uint32_t rel = key[e] - lo;
           atomicAdd(&hist[(key[e] > lo && rel <= span) ? rel >> shift : (uint32_t)kBins + (lane & 31)], 1u);
         }

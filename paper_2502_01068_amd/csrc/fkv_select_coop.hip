@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select_coop(SelectArgs a, CoopA
   __shared__ uint32_t slice_cnt[kCoopMaxSlices];  // keys of each slice inside the current interval
   __shared__ uint32_t hdr[2 * kCoopMaxSlices];    // (smallest key - 1, largest key) of each slice
   __shared__ uint32_t misc[8];  // 0 keys counted into the histogram, 1 kept / 2 tied list keys of earlier slices,
-                                // 3 a wave gave up, 4 verdict of the finish count, 5 / 6 list lengths of this slice
+                                // 3 a wave gave up, 4 outcome of the finish count, 5 list length of this slice
   static_assert(kCoopMaxSlices * kSelThreads <= kSelWaves * 64 * kMaxKpt, "peer staging fits the scan table");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

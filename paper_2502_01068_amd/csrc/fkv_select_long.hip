@@ -65,7 +65,7 @@ __device__ __forceinline__ LongRow locate_long(const SelectArgs &a) {
 }
 
 // Interval [lo, lo + 2^s) and rank after `rounds` completed rounds, from the state the previous
-// launches left: round 1 starts from the row's key range.
+// launches left: the first histogram launch starts from the row's key range.
 struct Interval { uint32_t lo, remaining, count; int s; };  // count: keys of the row inside the interval
 __device__ __forceinline__ Interval initial_interval(const LongRow &r) {
   Interval v;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_long_round(SelectArgs a) {
   uint32_t key[kLongKpt];
   load_keys<kLongKpt>(r.base, r.mis, r.P, r.slice * kLongChunk, wave, lane, key);
 
-  // interval before this round: from the key range (round 1) or from what round kRound-1 stored,
+  // interval before this round: from the key range (first histogram launch) or from what launch kRound-1 stored,
   // narrowed by the bin picked from that round's histogram
   Interval v;
   if (kRound <= 2) {
